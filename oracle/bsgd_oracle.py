@@ -1,0 +1,177 @@
+"""CPU oracle for one parameter-side step of synchronous SGD with backup
+workers (Algorithm 4 of the paper).
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 numpy statement of
+what the step computes.  It exists so the GPU library can be checked against
+something written independently from the paper; nothing in the product path
+may import it, and it imports nothing from the product path.
+
+What the step is, in the paper's notation:
+
+  * Algorithm 4, collect loop: the parameter side starts with an empty set,
+    waits for gradient messages and keeps those tagged with the current
+    step until it holds N of them; with N+b workers sending, the b slowest
+    messages are dropped when they arrive (Sec. 3, backup workers).
+  * Algorithm 4, update line: theta(t+1) = theta(t) - (gamma_t/N) * sum of the
+    kept gradients, i.e. one SGD update (Sec. 1.1) on the mean of the kept
+    mini-batch gradients.  Sec. 3 ("Sync-Opt") allows any first-order
+    optimizer in place of SGD; Appendix A.2/A.3 name RMSProp with momentum.
+  * Appendix A.3: clipping scales the gradient by its global norm taken over
+    all layers.
+
+Readings where the paper is silent (each is listed in the design notes):
+ties in arrival time go to the lower worker index; an arrival time of +inf
+or NaN means the message never arrives, and fewer than N arrivals means no
+update; momentum is v <- mu v + G, theta <- theta - gamma v; RMSProp with
+momentum is ms <- rho ms + (1-rho) G^2, m <- mu m + gamma G / sqrt(ms + eps),
+theta <- theta - m; clipping acts on the aggregated mean gradient with
+scale min(1, c/||G||).
+
+Pins (tests/test_oracle_*.py): numpy's stable argsort and an O(W^2)
+definition check for the selection, a message-queue simulation of the
+collect loop, the plain mean for b=0, exact rational arithmetic on tiny
+inputs, NaN-poisoned dropped rows, joint permutation of workers, closed-form
+SGD / momentum / RMSProp trajectories for constant gradients, numpy's norm
+for clipping.  No function here is unpinned.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+SGD, MOMENTUM, RMSPROP_MOM = "sgd", "momentum", "rmsprop_mom"
+
+
+# ----------------------------------------------------------------------------
+# Algorithm 4, collect loop
+# ----------------------------------------------------------------------------
+def select_first_n(arrival_t, N: int, b: int):
+    """Which N of the N+b gradients the parameter side keeps.
+
+    Algorithm 4 keeps messages in the order they arrive until it has N
+    (Sec. 3: "any N workers"; the slowest b are dropped).  Messages are
+    ordered by (arrival time, worker index); times are compared as the fp32
+    values given.  +inf / NaN = never arrives.
+
+    Returns (sel_idx int32[N] ascending, t_step fp32 = arrival time of the
+    N-th kept message) or None when fewer than N messages ever arrive.
+    """
+    t = np.asarray(arrival_t, dtype=np.float32)
+    W = N + b
+    if N < 1 or b < 0 or t.shape != (W,):
+        raise ValueError("arrival_t must hold N+b times, N >= 1, b >= 0")
+    when = [math.inf if math.isnan(float(x)) else float(x) for x in t]
+    order = sorted(range(W), key=lambda k: (when[k], k))
+    kept = order[:N]
+    last = kept[-1]
+    if when[last] == math.inf:
+        return None
+    return np.array(sorted(kept), dtype=np.int32), np.float32(when[last])
+
+
+# ----------------------------------------------------------------------------
+# Algorithm 4, update line: the mean of the kept gradients
+# ----------------------------------------------------------------------------
+def reduce_mean(grads, sel_idx: Sequence[int], lo: int = 0, hi: Optional[int] = None) -> np.ndarray:
+    """(1/N) * sum over kept workers k of G_k[lo:hi], in fp64.
+
+    `grads` is indexable as grads[k] -> fp32 row of worker k.  Only kept rows
+    are touched (dropped gradients play no part in the update)."""
+    N = len(sel_idx)
+    acc = None
+    for k in sel_idx:
+        row = np.asarray(grads[int(k)][lo:hi], dtype=np.float64)
+        acc = row.copy() if acc is None else acc + row
+    return acc / N
+
+
+# ----------------------------------------------------------------------------
+# Appendix A.3: clipping by the global norm over all layers
+# ----------------------------------------------------------------------------
+def clip_scale(gbars: Sequence[np.ndarray], c: float) -> float:
+    """min(1, c/||G||) with the 2-norm taken over every tensor together;
+    clipping is off for c <= 0 or c = +inf; a zero gradient is left alone."""
+    if not (c > 0.0) or math.isinf(c):
+        return 1.0
+    sq = 0.0
+    for g in gbars:
+        g = np.asarray(g, dtype=np.float64)
+        sq += float(np.dot(g, g))
+    nrm = math.sqrt(sq)
+    if nrm <= c:
+        return 1.0
+    return c / nrm
+
+
+# ----------------------------------------------------------------------------
+# optimizer updates on the aggregated gradient G (all in place, fp64)
+# ----------------------------------------------------------------------------
+def update_sgd(theta: np.ndarray, G: np.ndarray, lr: float) -> None:
+    """Sec. 1.1: theta(t+1) = theta(t) - gamma_t G(t)."""
+    theta -= lr * G
+
+
+def update_momentum(theta: np.ndarray, v: np.ndarray, G: np.ndarray, lr: float, mu: float) -> None:
+    """v <- mu v + G ; theta <- theta - gamma_t v (no dampening, no Nesterov)."""
+    v *= mu
+    v += G
+    theta -= lr * v
+
+
+def update_rmsprop_mom(theta: np.ndarray, ms: np.ndarray, m: np.ndarray, G: np.ndarray,
+                       lr: float, mu: float, rho: float, eps: float) -> None:
+    """RMSProp with momentum (Appendix A.2/A.3 give decay rho and momentum
+    mu): ms <- rho ms + (1-rho) G^2 ; m <- mu m + gamma_t G/sqrt(ms+eps) ;
+    theta <- theta - m."""
+    ms *= rho
+    ms += (1.0 - rho) * G * G
+    m *= mu
+    m += lr * G / np.sqrt(ms + eps)
+    theta -= m
+
+
+# ----------------------------------------------------------------------------
+# the whole step
+# ----------------------------------------------------------------------------
+def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> Tuple[bool, Optional[np.ndarray], Optional[np.float32]]:
+    """One parameter-side step.
+
+    grads      indexable by worker k -> fp32 row (length >= every offset+numel)
+    arrival_t  fp32[N+b]
+    tensors    list of dicts: 'theta' fp64[numel] (updated in place), 's0',
+               's1' fp64[numel] or None, 'grad_offset' int
+    hyper      dict: opt, lr, momentum, decay, eps, clip_norm
+
+    Returns (ok, sel_idx, t_step).  ok=False (fewer than N arrivals) leaves
+    every tensor untouched.
+    """
+    sel = select_first_n(arrival_t, N, b)
+    if sel is None:
+        return False, None, None
+    sel_idx, t_step = sel
+
+    gbars = []
+    for tz in tensors:
+        o = int(tz["grad_offset"])
+        n = tz["theta"].shape[0]
+        gbars.append(reduce_mean(grads, sel_idx, o, o + n))
+
+    s = clip_scale(gbars, float(hyper.get("clip_norm", 0.0)))
+    if s != 1.0:
+        gbars = [g * s for g in gbars]
+
+    opt = hyper["opt"]
+    lr = float(hyper["lr"])
+    for tz, G in zip(tensors, gbars):
+        if opt == SGD:
+            update_sgd(tz["theta"], G, lr)
+        elif opt == MOMENTUM:
+            update_momentum(tz["theta"], tz["s0"], G, lr, float(hyper["momentum"]))
+        elif opt == RMSPROP_MOM:
+            update_rmsprop_mom(tz["theta"], tz["s0"], tz["s1"], G, lr, float(hyper["momentum"]),
+                               float(hyper["decay"]), float(hyper["eps"]))
+        else:
+            raise ValueError(opt)
+    return True, sel_idx, t_step
