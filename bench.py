@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the backup-worker Sync-SGD step on one MI355X.
+
+A "step" is one whole pass of the hot path over one batch of synthetic
+input: arrival-order selection, gather-sum of the N kept gradient rows,
+mean, fused optimizer update.  The workload is configuration C2 (P = 25 M
+fp32 parameters in one tensor, N = 50 kept of 54 workers, RMSProp with
+momentum), the one the headline metric is quoted on.  Inputs are resident in
+HBM before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `value` is step throughput in
+GB/s of algorithmic bytes, (N*P + S*P)*4 per step with S = 6 state streams;
+`roofline` prices the dominant kernel alone against the 8 TB/s HBM peak;
+`cpu_baseline` times the CPU oracle on a bounded column sample of the same
+workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+STATE_STREAMS = {"sgd": 2, "momentum": 4, "rmsprop_mom": 6}
+
+
+def required_bytes(N: int, P: int, opt: str) -> int:
+    """Algorithmic HBM bytes of one step: N kept rows read once, theta and
+    optimizer state read once and written once."""
+    return (N * P + STATE_STREAMS[opt] * P) * 4
+
+
+def cpu_baseline(cfg, seconds_target: float = 15.0):
+    """The oracle as it stands (numpy, fp64, one thread) on a column sample."""
+    import numpy as np
+    import workloads as wl
+    from oracle import bsgd_oracle as orc
+
+    blocks = list(range(8))                                   # 8 x 65536 columns
+    n = sum(min(wl.BLOCK, cfg.P - b * wl.BLOCK) for b in blocks)
+    g = wl.grad_columns(cfg, 0, blocks)
+    hy = dict(opt=cfg.opt, lr=cfg.lr, momentum=cfg.momentum, decay=cfg.decay, eps=cfg.eps, clip_norm=0.0)
+    tz = [dict(theta=wl.theta0(cfg)[:n].astype(np.float64), s0=np.zeros(n), s1=np.zeros(n), grad_offset=0)]
+    # one untimed step, then as many as fit the target
+    orc.step(g, wl.arrival_times(cfg, 0), cfg.N, cfg.b, tz, hy)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        orc.step(g, wl.arrival_times(cfg, reps + 1), cfg.N, cfg.b, tz, hy)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= seconds_target or reps >= 200:
+            break
+    per_step_sample = dt / reps
+    gbs = required_bytes(cfg.N, n, cfg.opt) / per_step_sample / 1e9
+    full_step_s = per_step_sample * cfg.P / n
+    return {
+        "value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"{reps} steps of the fp64 numpy oracle on the first {n} of {cfg.P} columns, all {cfg.W} rows "
+                  f"({dt:.1f} s); scaled to the full width: {full_step_s:.2f} s/step, {1.0 / full_step_s:.3f} steps/s",
+        "steps_per_s_full_width": round(1.0 / full_step_s, 4),
+    }
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed
+    rocprofv3 counter summary, if one is present."""
+    p = os.path.join(ROOT, "profiles", "c2_reduce_update_traffic.json")
+    try:
+        with open(p) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2", help="workload (C2 is the headline; others for exploration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tuning", default="", help="vec,unroll,nontemporal override for the reduce kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the step shards along P across GPUs by design, "
+              "but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_1604_00981_amd as bs
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.tuning:
+        bs.bsgd_set_tuning(*[int(x) for x in args.tuning.split(",")])
+
+    cfg = wl.get_config(args.config)
+    offs, sizes, P = wl.tensor_layout(cfg)
+    T, N, b, W = len(sizes), cfg.N, cfg.b, cfg.W
+    K, Wm = args.steps, args.warmup
+    ld = (P + 3) // 4 * 4
+    ns = {"sgd": 0, "momentum": 1, "rmsprop_mom": 2}[cfg.opt]
+
+    # ---- inputs, resident in HBM before timing -------------------------------------------
+    t_gen = time.perf_counter()
+    g_pin = torch.zeros((W, ld), dtype=torch.float32, pin_memory=True)
+    wl.grad_matrix(cfg, 0, out=g_pin.numpy(), ld=ld)
+    grads = g_pin.cuda()
+    del g_pin
+    theta = torch.from_numpy(wl.theta0(cfg)).cuda()
+    state = [torch.zeros(P, device="cuda") for _ in range(ns)]
+    arrivals = torch.from_numpy(np.stack([wl.arrival_times(cfg, s) for s in range(Wm + 2 * K)])).cuda()
+    items = [(theta[o:o + n], state[0][o:o + n] if ns > 0 else None, state[1][o:o + n] if ns > 1 else None, o, n)
+             for o, n in zip(offs, sizes)]
+    tensors = bs.make_tensors(items)
+    hyper = bs.make_hyper(cfg.opt, cfg.lr, cfg.momentum, cfg.decay, cfg.eps, cfg.clip_norm)
+    ws = bs.alloc_workspace(P, N, b, T, hyper)
+    sel = torch.zeros(N, dtype=torch.int32, device="cuda")
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t_gen
+
+    stream = torch.cuda.current_stream()
+
+    # ---- warm-up ---------------------------------------------------------------------------
+    for i in range(Wm):
+        bs.bsgd_step(grads, ld, arrivals[i], N, b, tensors, hyper, ws)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K whole steps -------------------------------------------------
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(K):
+        bs.bsgd_step(grads, ld, arrivals[Wm + i], N, b, tensors, hyper, ws)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / K
+    status, _ = bs.bsgd_last_status(ws)
+    if status != 0:
+        print(f"bench.py: step reported status {status}", file=sys.stderr)
+        return 1
+
+    # ---- the dominant kernel alone: same steps, events around the reduce/update launch ---------
+    ka = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    kb = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    for i in range(K):
+        bs.bsgd_select_first_n(arrivals[Wm + K + i], N, b, sel, None, st)
+        ka[i].record(stream)
+        bs.bsgd_reduce_update(grads, ld, sel, st, N, tensors, hyper, ws)
+        kb[i].record(stream)
+    torch.cuda.synchronize()
+    kernel_ms = sum(a.elapsed_time(c) for a, c in zip(ka, kb)) / K
+
+    req = required_bytes(N, P, cfg.opt)
+    gbs = req / (ms_per_step * 1e-3) / 1e9
+    achieved = req / (kernel_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "step GB/s and % of HBM peak at P=25M N=50 b=4 (fused RMSProp); steps/sec",
+        "value": round(gbs, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: P={P} fp32 in {T} tensor(s), N={N} kept of {W} workers, {cfg.opt}"
+                               + (f", clip {cfg.clip_norm}" if cfg.clip_norm > 0 else ""),
+                   "P": P, "N": N, "b": b, "T": T, "optimizer": cfg.opt, "ld": ld,
+                   "required_bytes_per_step": req},
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "steps_per_s": round(1e3 / ms_per_step, 2),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
+                     "kernel": "k_step (reduce + fused update)", "kernel_ms": round(kernel_ms, 5),
+                     "algorithmic_bytes_per_launch": req},
+        "input_setup_s": round(gen_s, 2),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,165 @@
+/*
+ * bsgd — the parameter-side step of synchronous SGD with backup workers,
+ * for one AMD MI355X (gfx950).
+ *
+ * What one step computes (paper: "Revisiting Distributed Synchronous SGD",
+ * Algorithm 4, and Sec. 3 "backup workers"):
+ *
+ *   1. N+b workers each send a gradient G_k for the current step.  The
+ *      parameter side keeps the first N to arrive and drops the b slowest
+ *      (Algorithm 4, collect loop).
+ *   2. theta(t+1) = theta(t) - (gamma_t / N) * sum of the kept G_k
+ *      (Algorithm 4, update line), i.e. one optimizer update on the mean of
+ *      the kept mini-batch gradients (Sec. 1.1 notation: theta, G, gamma_t).
+ *      Sec. 3 allows any first-order optimizer in place of plain SGD;
+ *      Appendix A.2/A.3 use RMSProp with momentum.
+ *   3. Optionally the aggregated gradient is first clipped by its global L2
+ *      norm over all layers (Appendix A.3 describes global-norm clipping).
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are HIP device pointers valid on the current
+ *     device; pointers marked HOST are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on `stream` and return; they never synchronise
+ *     unless stated.  HOST arrays are consumed before the call returns.
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and keeps no pointer after a call returns.
+ *   - Return value: BSGD_OK, or a negative BSGD_ERR_* for misuse detectable
+ *     on the host (nothing is enqueued then).  The one condition only the
+ *     device can see — fewer than N workers ever arrive — is reported
+ *     through a device status word and leaves theta and state untouched.
+ *   - All floating-point data is IEEE fp32, gradients row-major.
+ */
+#ifndef BSGD_H
+#define BSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BSGD_OK            0
+#define BSGD_ERR_ARG      (-1)  /* bad argument (host-detected)                     */
+#define BSGD_ERR_TOO_FEW  (-2)  /* device status: fewer than N gradients arrive     */
+#define BSGD_ERR_HIP      (-3)  /* a HIP runtime call failed                        */
+
+#define BSGD_MAX_WORKERS  256   /* N + b may not exceed this                        */
+#define BSGD_MAX_TENSORS  8192  /* T may not exceed this                            */
+
+/* Which update rule is applied to the aggregated gradient G (Sec. 3:
+ * "Sync-Opt"; Sec. 1.1 gives SGD, Appendix A.2/A.3 name RMSProp with
+ * momentum and its decay/momentum values).
+ *   BSGD_SGD          theta <- theta - lr*G
+ *   BSGD_MOMENTUM     v  <- momentum*v + G ;              theta <- theta - lr*v
+ *   BSGD_RMSPROP_MOM  ms <- decay*ms + (1-decay)*G*G ;
+ *                     m  <- momentum*m + lr*G/sqrt(ms+eps) ; theta <- theta - m   */
+typedef enum { BSGD_SGD = 0, BSGD_MOMENTUM = 1, BSGD_RMSPROP_MOM = 2 } bsgd_opt;
+
+/* Hyper-parameters of one step.  HOST; read during the call. */
+typedef struct {
+  int32_t opt;        /* bsgd_opt                                                   */
+  float   lr;         /* gamma_t for THIS step (schedules belong to the caller)     */
+  float   momentum;   /* mu   (BSGD_MOMENTUM, BSGD_RMSPROP_MOM)                     */
+  float   decay;      /* rho  (BSGD_RMSPROP_MOM)                                    */
+  float   eps;        /* epsilon, added inside the square root (BSGD_RMSPROP_MOM)   */
+  float   clip_norm;  /* c: G <- G*min(1, c/||G||_2), norm over all tensors;
+                         <= 0, NaN or +inf switches clipping off                    */
+} bsgd_hyper;
+
+/* One parameter tensor.  The struct array itself is HOST memory; the
+ * pointers inside are DEVICE pointers, 4-byte aligned, updated in place. */
+typedef struct {
+  float*  theta;        /* numel parameters                                         */
+  float*  s0;           /* v (BSGD_MOMENTUM) or ms (BSGD_RMSPROP_MOM); else NULL     */
+  float*  s1;           /* m (BSGD_RMSPROP_MOM); else NULL                          */
+  int64_t grad_offset;  /* where this tensor starts inside every gradient row       */
+  int64_t numel;        /* >= 0                                                     */
+} bsgd_tensor;
+
+/* Algorithm 4, collect loop: which N of the N+b gradients are kept.
+ *
+ *   arrival_t  DEVICE fp32[N+b]: arrival time of worker k's gradient in this
+ *              step.  +inf or NaN = never arrives (also stands for a message
+ *              carrying a stale step tag, which Algorithm 4 drops).
+ *   sel_idx    DEVICE out int32[N]: kept workers, ascending index.
+ *   t_step     DEVICE out fp32 (may be NULL): arrival time of the N-th kept
+ *              gradient, i.e. how long the step waited.
+ *   status     DEVICE out int32: BSGD_OK, or BSGD_ERR_TOO_FEW when fewer than
+ *              N arrival times are finite (sel_idx contents are then unspecified).
+ *
+ * Workers are ordered by (arrival time, worker index): equal times go to the
+ * lower index; -0 and +0 are the same instant.  Errors: BSGD_ERR_ARG for
+ * N < 1, b < 0, N+b > BSGD_MAX_WORKERS or a NULL required pointer. */
+int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b,
+                        int32_t* sel_idx, float* t_step, int32_t* status, void* stream);
+
+/* Algorithm 4, update line, for an already chosen set: sum the N kept rows,
+ * take the mean, optionally clip, apply one optimizer update to every tensor.
+ *
+ *   grads     DEVICE fp32[(N+b) x ld], row k = worker k's gradient; only rows
+ *             listed in sel_idx are read.  Must not alias theta/state.
+ *   ld        row stride in elements, >= every grad_offset + numel.
+ *   sel_idx   DEVICE int32[N] (as written by bsgd_select_first_n), values in [0, N+b).
+ *   status    DEVICE int32 or NULL: when non-NULL and the word is non-zero at
+ *             execution time the kernels do nothing.
+ *   tensors   HOST array of T descriptors (T = 1 for one flat theta).
+ *   workspace DEVICE scratch of at least bsgd_workspace_bytes(...) bytes,
+ *             256-byte aligned; contents need not be preserved between calls.
+ *
+ * Rows are added in ascending worker index in fp32, the sum is multiplied by
+ * 1/N once.  Errors: BSGD_ERR_ARG for bad sizes, NULL pointers, a missing
+ * state pointer for the chosen optimizer, ld too small or a workspace too
+ * small.  Overlap between tensors is not checked. */
+int bsgd_reduce_update(const float* grads, int64_t ld,
+                       const int32_t* sel_idx, const int32_t* status, int32_t N,
+                       const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* One whole step of Algorithm 4: bsgd_select_first_n into the workspace,
+ * then bsgd_reduce_update with that selection.  Arguments as above.  When
+ * fewer than N gradients arrive, theta and state are left untouched and the
+ * workspace status word holds BSGD_ERR_TOO_FEW (see bsgd_last_status). */
+int bsgd_step(const float* grads, int64_t ld,
+              const float* arrival_t, int32_t N, int32_t b,
+              const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace bsgd_step / bsgd_reduce_update need.  span = the largest
+ * grad_offset + numel over the tensors (the total parameter count when the
+ * tensors are packed back to back).  Returns 0 for invalid arguments. */
+size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const bsgd_hyper* hyper);
+
+/* Synchronises `stream`, then copies out what the last bsgd_step on this
+ * workspace recorded.  Any out pointer may be NULL.
+ *   status_out  HOST int32: BSGD_OK or BSGD_ERR_TOO_FEW
+ *   t_step_out  HOST fp32: arrival time of the N-th kept gradient          */
+int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out);
+
+/* Synchronises `stream`, then copies the N kept worker indices of the last
+ * bsgd_step on this workspace to HOST int32[N]. */
+int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t* sel_idx_out);
+
+/* Synchronises `stream`, then reports the global norm ||G|| (before
+ * clipping) and the scale applied by the last clipped step on this
+ * workspace.  HOST out pointers, either may be NULL. */
+int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float* scale_out);
+
+/* Launch-shape tuning for the reduce/update kernel, process-wide; for
+ * benchmarking.  vec = float4 columns per thread (1, 2 or 4), unroll = rows
+ * in flight per batch (4, 8 or 16), nontemporal = 0/1 streaming loads of the
+ * gradient rows.  A value of -1 keeps the built-in choice.  Returns
+ * BSGD_ERR_ARG for a combination that is not compiled in. */
+int bsgd_set_tuning(int32_t vec, int32_t unroll, int32_t nontemporal);
+
+/* Human-readable text for a BSGD_* code. */
+const char* bsgd_strerror(int code);
+
+/* Library version string, e.g. "bsgd 0.1 (gfx950)". */
+const char* bsgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSGD_H */

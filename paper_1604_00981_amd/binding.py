@@ -1,0 +1,225 @@
+"""ctypes binding of libbsgd.so: same names as the C entry points in
+include/bsgd.h, argument marshalling only.  Every step of the path runs in
+the HIP kernels; there is no CPU fallback, and a missing library is an error.
+
+PyTorch is used for device memory and streams: arguments are CUDA/HIP
+tensors (or raw device addresses as ints) and the launch goes to torch's
+current stream unless one is given.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Iterable, List, Optional, Sequence, Tuple, Union
+
+import torch  # imported before the library so both share one HIP runtime
+
+from . import build as _build
+
+BSGD_OK = 0
+BSGD_ERR_ARG = -1
+BSGD_ERR_TOO_FEW = -2
+BSGD_ERR_HIP = -3
+BSGD_MAX_WORKERS = 256
+BSGD_MAX_TENSORS = 8192
+
+BSGD_SGD, BSGD_MOMENTUM, BSGD_RMSPROP_MOM = 0, 1, 2
+_OPT_BY_NAME = {"sgd": BSGD_SGD, "momentum": BSGD_MOMENTUM, "rmsprop_mom": BSGD_RMSPROP_MOM}
+
+
+class bsgd_hyper(ctypes.Structure):
+    _fields_ = [("opt", ctypes.c_int32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
+                ("decay", ctypes.c_float), ("eps", ctypes.c_float), ("clip_norm", ctypes.c_float)]
+
+
+class bsgd_tensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("s0", ctypes.c_void_p), ("s1", ctypes.c_void_p),
+                ("grad_offset", ctypes.c_int64), ("numel", ctypes.c_int64)]
+
+
+class BsgdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libbsgd.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _build.LIB_PATH
+    if not os.path.exists(p):
+        if path is not None:
+            raise FileNotFoundError(p)
+        _build.build_library(verbose=False)
+    lib = ctypes.CDLL(p)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.bsgd_select_first_n.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.bsgd_select_first_n.restype = ctypes.c_int
+    lib.bsgd_reduce_update.argtypes = [vp, i64, vp, vp, i32, ctypes.POINTER(bsgd_tensor), i32,
+                                       ctypes.POINTER(bsgd_hyper), vp, sz, vp]
+    lib.bsgd_reduce_update.restype = ctypes.c_int
+    lib.bsgd_step.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_tensor), i32,
+                              ctypes.POINTER(bsgd_hyper), vp, sz, vp]
+    lib.bsgd_step.restype = ctypes.c_int
+    lib.bsgd_workspace_bytes.argtypes = [i64, i32, i32, i32, ctypes.POINTER(bsgd_hyper)]
+    lib.bsgd_workspace_bytes.restype = sz
+    lib.bsgd_last_status.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float)]
+    lib.bsgd_last_status.restype = ctypes.c_int
+    lib.bsgd_last_selection.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
+    lib.bsgd_last_selection.restype = ctypes.c_int
+    lib.bsgd_last_clip.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float)]
+    lib.bsgd_last_clip.restype = ctypes.c_int
+    lib.bsgd_set_tuning.argtypes = [i32, i32, i32]
+    lib.bsgd_set_tuning.restype = ctypes.c_int
+    lib.bsgd_strerror.argtypes = [ctypes.c_int]
+    lib.bsgd_strerror.restype = ctypes.c_char_p
+    lib.bsgd_version.argtypes = []
+    lib.bsgd_version.restype = ctypes.c_char_p
+    if path is None:
+        _lib = lib
+    return lib
+
+
+# ----------------------------------------------------------------------------
+# marshalling helpers
+# ----------------------------------------------------------------------------
+DevPtr = Union[torch.Tensor, int, None]
+
+
+def _ptr(x: DevPtr, dtype: Optional[torch.dtype] = None, name: str = "arg") -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if not isinstance(x, torch.Tensor):
+        raise TypeError(f"{name}: expected a device tensor or an address")
+    if not x.is_cuda:
+        raise ValueError(f"{name}: must live on the GPU")
+    if dtype is not None and x.dtype != dtype:
+        raise ValueError(f"{name}: expected {dtype}, got {x.dtype}")
+    if not x.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return x.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def make_hyper(opt, lr: float, momentum: float = 0.0, decay: float = 0.0, eps: float = 0.0,
+               clip_norm: float = 0.0) -> bsgd_hyper:
+    code = _OPT_BY_NAME[opt] if isinstance(opt, str) else int(opt)
+    return bsgd_hyper(code, lr, momentum, decay, eps, clip_norm)
+
+
+def make_tensors(items: Iterable[Tuple[DevPtr, DevPtr, DevPtr, int, int]]):
+    """ctypes array of bsgd_tensor from (theta, s0, s1, grad_offset, numel)."""
+    items = list(items)
+    arr = (bsgd_tensor * len(items))()
+    for d, (theta, s0, s1, off, numel) in zip(arr, items):
+        d.theta = _ptr(theta, torch.float32, "theta")
+        d.s0 = _ptr(s0, torch.float32, "s0")
+        d.s1 = _ptr(s1, torch.float32, "s1")
+        d.grad_offset = int(off)
+        d.numel = int(numel)
+    return arr
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != BSGD_OK:
+        raise BsgdError(rc, where)
+
+
+# ----------------------------------------------------------------------------
+# entry points (same names as the C ABI)
+# ----------------------------------------------------------------------------
+def bsgd_select_first_n(arrival_t: DevPtr, N: int, b: int, sel_idx: DevPtr, t_step: DevPtr, status: DevPtr,
+                        stream=None) -> None:
+    lib = load_library()
+    _check(lib.bsgd_select_first_n(_ptr(arrival_t, torch.float32, "arrival_t"), N, b,
+                                   _ptr(sel_idx, torch.int32, "sel_idx"), _ptr(t_step, torch.float32, "t_step"),
+                                   _ptr(status, torch.int32, "status"), _stream(stream)), "bsgd_select_first_n")
+
+
+def _ws(workspace: DevPtr, workspace_bytes: Optional[int]) -> Tuple[int, int]:
+    if isinstance(workspace, torch.Tensor):
+        n = workspace.numel() * workspace.element_size()
+        return _ptr(workspace, None, "workspace"), n if workspace_bytes is None else workspace_bytes
+    if workspace_bytes is None:
+        raise ValueError("workspace_bytes is required with a raw workspace address")
+    return workspace, workspace_bytes
+
+
+def bsgd_reduce_update(grads: DevPtr, ld: int, sel_idx: DevPtr, status: DevPtr, N: int, tensors, hyper: bsgd_hyper,
+                       workspace: DevPtr, workspace_bytes: Optional[int] = None, stream=None) -> None:
+    lib = load_library()
+    ws, nbytes = _ws(workspace, workspace_bytes)
+    _check(lib.bsgd_reduce_update(_ptr(grads, torch.float32, "grads"), ld, _ptr(sel_idx, torch.int32, "sel_idx"),
+                                  _ptr(status, torch.int32, "status"), N, tensors, len(tensors),
+                                  ctypes.byref(hyper), ws, nbytes, _stream(stream)), "bsgd_reduce_update")
+
+
+def bsgd_step(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, tensors, hyper: bsgd_hyper,
+              workspace: DevPtr, workspace_bytes: Optional[int] = None, stream=None) -> None:
+    lib = load_library()
+    ws, nbytes = _ws(workspace, workspace_bytes)
+    _check(lib.bsgd_step(_ptr(grads, torch.float32, "grads"), ld, _ptr(arrival_t, torch.float32, "arrival_t"),
+                         N, b, tensors, len(tensors), ctypes.byref(hyper), ws, nbytes, _stream(stream)), "bsgd_step")
+
+
+def bsgd_workspace_bytes(span: int, N: int, b: int, T: int, hyper: bsgd_hyper) -> int:
+    n = load_library().bsgd_workspace_bytes(span, N, b, T, ctypes.byref(hyper))
+    if n == 0:
+        raise BsgdError(BSGD_ERR_ARG, "bsgd_workspace_bytes")
+    return n
+
+
+def bsgd_last_status(workspace: DevPtr, stream=None) -> Tuple[int, float]:
+    st, ts = ctypes.c_int32(0), ctypes.c_float(0.0)
+    _check(load_library().bsgd_last_status(_ptr(workspace, None, "workspace"), _stream(stream),
+                                           ctypes.byref(st), ctypes.byref(ts)), "bsgd_last_status")
+    return st.value, ts.value
+
+
+def bsgd_last_selection(workspace: DevPtr, N: int, stream=None) -> List[int]:
+    out = (ctypes.c_int32 * N)()
+    _check(load_library().bsgd_last_selection(_ptr(workspace, None, "workspace"), _stream(stream), N, out),
+           "bsgd_last_selection")
+    return list(out)
+
+
+def bsgd_last_clip(workspace: DevPtr, stream=None) -> Tuple[float, float]:
+    nrm, sc = ctypes.c_double(0.0), ctypes.c_float(0.0)
+    _check(load_library().bsgd_last_clip(_ptr(workspace, None, "workspace"), _stream(stream),
+                                         ctypes.byref(nrm), ctypes.byref(sc)), "bsgd_last_clip")
+    return nrm.value, sc.value
+
+
+def bsgd_set_tuning(vec: int = -1, unroll: int = -1, nontemporal: int = -1) -> None:
+    _check(load_library().bsgd_set_tuning(vec, unroll, nontemporal), "bsgd_set_tuning")
+
+
+def strerror(code: int) -> str:
+    return load_library().bsgd_strerror(code).decode()
+
+
+def bsgd_version() -> str:
+    return load_library().bsgd_version().decode()
+
+
+def alloc_workspace(span: int, N: int, b: int, T: int, hyper: bsgd_hyper, device="cuda") -> torch.Tensor:
+    """A torch uint8 buffer of the size the library asks for (torch's caching
+    allocator hands out 512-byte aligned blocks)."""
+    n = bsgd_workspace_bytes(span, N, b, T, hyper)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    assert ws.data_ptr() % 256 == 0
+    return ws

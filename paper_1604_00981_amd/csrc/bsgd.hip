@@ -1,0 +1,311 @@
+// Host side of libbsgd: argument checks, workspace carving and kernel
+// launches for the entry points declared in bsgd.h.  Every entry point only
+// enqueues work on the caller's stream.
+#include "bsgd_kernels.hpp"
+
+#include "../../include/bsgd.h"
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+using namespace bsgd;
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// workspace layout (all offsets multiples of 256 bytes)
+//   [0,256)            WsHeader
+//   [256,1280)         sel_idx int32[256]
+//   then               DevTensor table[T], chunk_begin int32[T+1]
+//   clipped steps:     partials double[max_chunks], gbar float[span rounded up]
+// ---------------------------------------------------------------------------
+constexpr size_t kAlign = 256;
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct WsLayout {
+  size_t sel_off, table_off, cb_off, partials_off, gbar_off, total;
+  long long max_chunks;
+};
+
+constexpr int kMinChunkElems = 4 * kBlock;            // V = 1
+
+bool clip_on(const bsgd_hyper* h) { return h && h->clip_norm > 0.0f && std::isfinite(h->clip_norm); }
+
+WsLayout layout(long long span, int T, bool clip) {
+  WsLayout L{};
+  L.sel_off = kAlign;
+  L.table_off = L.sel_off + round_up(sizeof(int) * kMaxWorkers, kAlign);
+  L.cb_off = L.table_off + round_up(sizeof(DevTensor) * (size_t)T, kAlign);
+  L.partials_off = L.cb_off + round_up(sizeof(int) * ((size_t)T + 1), kAlign);
+  // every tensor adds at most two partly filled chunks on top of span/chunk
+  L.max_chunks = span / kMinChunkElems + 2LL * T + 2;
+  L.gbar_off = L.partials_off;
+  L.total = L.partials_off;
+  if (clip) {
+    L.gbar_off = L.partials_off + round_up(sizeof(double) * (size_t)L.max_chunks, kAlign);
+    L.total = L.gbar_off + round_up(sizeof(float) * ((size_t)span + 4), kAlign);
+  }
+  return L;
+}
+
+// ---------------------------------------------------------------------------
+// kernel variants
+// ---------------------------------------------------------------------------
+using StepKernel = void (*)(StepParams);
+
+struct Variant {
+  int V, U, NT;
+  StepKernel rows[4][2];     // [mode][multi]
+};
+
+#define BSGD_ROWS(V, U, NT)                                                                            \
+  {V, U, NT,                                                                                           \
+   {{k_step<kSgd, V, U, NT != 0, false, true>, k_step<kSgd, V, U, NT != 0, true, true>},               \
+    {k_step<kMomentum, V, U, NT != 0, false, true>, k_step<kMomentum, V, U, NT != 0, true, true>},     \
+    {k_step<kRmspropMom, V, U, NT != 0, false, true>, k_step<kRmspropMom, V, U, NT != 0, true, true>}, \
+    {k_step<kClipReduce, V, U, NT != 0, false, true>, k_step<kClipReduce, V, U, NT != 0, true, true>}}}
+
+const Variant kVariants[] = {
+    BSGD_ROWS(1, 16, 1), BSGD_ROWS(1, 8, 1), BSGD_ROWS(2, 8, 1), BSGD_ROWS(2, 16, 1),
+    BSGD_ROWS(4, 4, 1),  BSGD_ROWS(4, 8, 1), BSGD_ROWS(1, 16, 0), BSGD_ROWS(2, 8, 0),
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+struct ApplyVariant {
+  int V;
+  StepKernel apply[3][2];    // [mode][multi]
+};
+#define BSGD_APPLY(V)                                                                              \
+  {V,                                                                                              \
+   {{k_step<kSgd, V, 1, false, false, false>, k_step<kSgd, V, 1, false, true, false>},             \
+    {k_step<kMomentum, V, 1, false, false, false>, k_step<kMomentum, V, 1, false, true, false>},   \
+    {k_step<kRmspropMom, V, 1, false, false, false>, k_step<kRmspropMom, V, 1, false, true, false>}}}
+const ApplyVariant kApply[] = {BSGD_APPLY(1), BSGD_APPLY(2), BSGD_APPLY(4)};
+
+std::atomic<int> g_variant{0};
+
+const ApplyVariant* apply_for(int V) {
+  for (const ApplyVariant& a : kApply)
+    if (a.V == V) return &a;
+  return nullptr;
+}
+
+int launch(StepKernel fn, long long grid, size_t lds, hipStream_t stream, StepParams& p) {
+  if (grid <= 0) return BSGD_OK;
+  if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
+  void* args[] = {&p};
+  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(kBlock), args, lds, stream);
+  return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
+bool check_select_args(const float* arrival_t, int N, int b) {
+  return arrival_t != nullptr && N >= 1 && b >= 0 && (long long)N + b <= BSGD_MAX_WORKERS;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b, int32_t* sel_idx, float* t_step,
+                        int32_t* status, void* stream) {
+  if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr) return BSGD_ERR_ARG;
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(64), 0, (hipStream_t)stream, arrival_t, (int)N, (int)(N + b),
+                     (int*)sel_idx, t_step, (int*)status);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
+size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const bsgd_hyper* hyper) {
+  if (span < 0 || N < 1 || b < 0 || (long long)N + b > BSGD_MAX_WORKERS || T < 1 || T > BSGD_MAX_TENSORS ||
+      hyper == nullptr)
+    return 0;
+  return layout(span, T, clip_on(hyper)).total;
+}
+
+// Host-only validation shared by bsgd_reduce_update and bsgd_step: nothing is
+// enqueued unless this passes.
+static int validate_update_args(const float* grads, int64_t ld, int32_t N, const bsgd_tensor* tensors, int32_t T,
+                                const bsgd_hyper* hyper, const void* workspace, size_t workspace_bytes,
+                                long long* span_out) {
+  if (grads == nullptr || tensors == nullptr || hyper == nullptr || workspace == nullptr) return BSGD_ERR_ARG;
+  if (N < 1 || N > BSGD_MAX_WORKERS || T < 1 || T > BSGD_MAX_TENSORS || ld < 0) return BSGD_ERR_ARG;
+  if (hyper->opt < BSGD_SGD || hyper->opt > BSGD_RMSPROP_MOM) return BSGD_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return BSGD_ERR_ARG;
+  // Row loads are aligned 16-byte accesses: the gradient base must be 16-byte
+  // aligned and the row stride a multiple of 4 elements.
+  if ((reinterpret_cast<uintptr_t>(grads) & 15) != 0 || (ld & 3) != 0) return BSGD_ERR_ARG;
+  const int mode = hyper->opt;
+  long long span = 0;
+  for (int j = 0; j < T; ++j) {
+    const bsgd_tensor& t = tensors[j];
+    if (t.numel < 0 || t.grad_offset < 0) return BSGD_ERR_ARG;
+    if (t.numel == 0) continue;
+    if (t.theta == nullptr || (reinterpret_cast<uintptr_t>(t.theta) & 3)) return BSGD_ERR_ARG;
+    if (mode >= BSGD_MOMENTUM && (t.s0 == nullptr || (reinterpret_cast<uintptr_t>(t.s0) & 3))) return BSGD_ERR_ARG;
+    if (mode == BSGD_RMSPROP_MOM && (t.s1 == nullptr || (reinterpret_cast<uintptr_t>(t.s1) & 3))) return BSGD_ERR_ARG;
+    if (t.grad_offset > ld - t.numel) return BSGD_ERR_ARG;
+    if (t.grad_offset + t.numel > span) span = t.grad_offset + t.numel;
+  }
+  const WsLayout L = layout(span, T, clip_on(hyper));
+  if (workspace_bytes < L.total) return BSGD_ERR_ARG;
+  // chunk ids are 32-bit
+  if (span / kMinChunkElems + 2LL * T + 2 > 0x7fffffffLL) return BSGD_ERR_ARG;
+  *span_out = span;
+  return BSGD_OK;
+}
+
+static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
+                          const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
+                          long long span, hipStream_t stream) {
+  const int mode = hyper->opt;
+  const bool clip = clip_on(hyper);
+  const WsLayout L = layout(span, T, clip);
+  char* ws = static_cast<char*>(workspace);
+  const Variant& var = kVariants[g_variant.load(std::memory_order_relaxed)];
+  const int V = var.V;
+  const long long chunk_groups = (long long)kBlock * V;
+
+  StepParams p{};
+  p.grads = grads;
+  p.ld = ld;
+  p.sel_idx = sel_idx;
+  p.status = status;
+  p.N = N;
+  p.inv_n = 1.0f / (float)N;
+  p.lr = hyper->lr;
+  p.mu = hyper->momentum;
+  p.rho = hyper->decay;
+  p.one_minus_rho = (float)(1.0 - (double)hyper->decay);
+  p.eps = hyper->eps;
+  p.gbar = reinterpret_cast<float*>(ws + L.gbar_off);
+  p.partials = reinterpret_cast<double*>(ws + L.partials_off);
+  p.header = reinterpret_cast<const WsHeader*>(ws);
+  p.table = reinterpret_cast<const DevTensor*>(ws + L.table_off);
+  p.chunk_begin = reinterpret_cast<const int*>(ws + L.cb_off);
+  p.T = T;
+
+  auto chunks_of = [&](const bsgd_tensor& t) -> long long {
+    if (t.numel == 0) return 0;
+    const long long groups = ((t.grad_offset & 3) + t.numel + 3) / 4;
+    return (groups + chunk_groups - 1) / chunk_groups;
+  };
+
+  long long total_chunks = 0;
+  const bool multi = T > 1;
+  size_t lds = 0;
+  if (!multi) {
+    const bsgd_tensor& t = tensors[0];
+    p.single = DevTensor{t.theta, t.s0, t.s1, t.grad_offset, t.numel};
+    total_chunks = chunks_of(t);
+  } else {
+    DevTensor* d_table = reinterpret_cast<DevTensor*>(ws + L.table_off);
+    int* d_cb = reinterpret_cast<int*>(ws + L.cb_off);
+    for (int first = 0; first < T; first += kUploadBatch) {
+      UploadArgs a{};
+      a.first = first;
+      a.count = (T - first < kUploadBatch) ? (T - first) : kUploadBatch;
+      for (int i = 0; i < a.count; ++i) {
+        const bsgd_tensor& t = tensors[first + i];
+        a.t[i] = DevTensor{t.theta, t.s0, t.s1, t.grad_offset, t.numel};
+        a.chunk_begin[i] = (int)total_chunks;
+        total_chunks += chunks_of(t);
+      }
+      a.is_last = (first + a.count == T);
+      a.total_chunks = (int)total_chunks;
+      hipLaunchKernelGGL(k_upload_table, dim3(1), dim3(kUploadBatch), 0, stream, a, d_table, d_cb, (int)T);
+      if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+    }
+    lds = sizeof(int) * ((size_t)T + 1);
+  }
+
+  if (!clip) return launch(var.rows[mode][multi ? 1 : 0], total_chunks, lds, stream, p);
+
+  int rc = launch(var.rows[kClipReduce][multi ? 1 : 0], total_chunks, lds, stream, p);
+  if (rc != BSGD_OK) return rc;
+  hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
+                     (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
+  if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  const ApplyVariant* av = apply_for(V);
+  if (av == nullptr) return BSGD_ERR_ARG;
+  return launch(av->apply[mode][multi ? 1 : 0], total_chunks, lds, stream, p);
+}
+
+int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
+                       const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (sel_idx == nullptr) return BSGD_ERR_ARG;
+  long long span = 0;
+  int rc = validate_update_args(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &span);
+  if (rc != BSGD_OK) return rc;
+  return enqueue_update(grads, ld, sel_idx, status, N, tensors, T, hyper, workspace, span, (hipStream_t)stream);
+}
+
+int bsgd_step(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
+              const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
+              size_t workspace_bytes, void* stream) {
+  if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
+  long long span = 0;
+  int rc = validate_update_args(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &span);
+  if (rc != BSGD_OK) return rc;
+  char* ws = static_cast<char*>(workspace);
+  WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
+  int* sel = reinterpret_cast<int*>(ws + kAlign);
+  rc = bsgd_select_first_n(arrival_t, N, b, sel, &hdr->t_step, &hdr->status, stream);
+  if (rc != BSGD_OK) return rc;
+  return enqueue_update(grads, ld, sel, &hdr->status, N, tensors, T, hyper, workspace, span, (hipStream_t)stream);
+}
+
+int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out) {
+  if (workspace == nullptr) return BSGD_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BSGD_ERR_HIP;
+  WsHeader h;
+  if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
+  if (status_out) *status_out = h.status;
+  if (t_step_out) *t_step_out = h.t_step;
+  return BSGD_OK;
+}
+
+int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t* sel_idx_out) {
+  if (workspace == nullptr || sel_idx_out == nullptr || N < 1 || N > BSGD_MAX_WORKERS) return BSGD_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BSGD_ERR_HIP;
+  if (hipMemcpy(sel_idx_out, static_cast<const char*>(workspace) + kAlign, sizeof(int) * (size_t)N,
+                hipMemcpyDeviceToHost) != hipSuccess)
+    return BSGD_ERR_HIP;
+  return BSGD_OK;
+}
+
+int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float* scale_out) {
+  if (workspace == nullptr) return BSGD_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BSGD_ERR_HIP;
+  WsHeader h;
+  if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
+  if (norm_out) *norm_out = h.norm;
+  if (scale_out) *scale_out = h.clip_scale;
+  return BSGD_OK;
+}
+
+int bsgd_set_tuning(int32_t vec, int32_t unroll, int32_t nontemporal) {
+  const Variant& cur = kVariants[g_variant.load(std::memory_order_relaxed)];
+  const int V = vec < 0 ? cur.V : vec, U = unroll < 0 ? cur.U : unroll, NT = nontemporal < 0 ? cur.NT : nontemporal;
+  for (int i = 0; i < kNumVariants; ++i) {
+    if (kVariants[i].V == V && kVariants[i].U == U && kVariants[i].NT == NT) {
+      g_variant.store(i, std::memory_order_relaxed);
+      return BSGD_OK;
+    }
+  }
+  return BSGD_ERR_ARG;
+}
+
+const char* bsgd_strerror(int code) {
+  switch (code) {
+    case BSGD_OK: return "ok";
+    case BSGD_ERR_ARG: return "invalid argument";
+    case BSGD_ERR_TOO_FEW: return "fewer than N gradients arrived; parameters left untouched";
+    case BSGD_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown bsgd code";
+  }
+}
+
+const char* bsgd_version(void) { return "bsgd 0.1 (gfx950)"; }
+
+}  // extern "C"

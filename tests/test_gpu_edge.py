@@ -1,0 +1,301 @@
+"""GPU edge cases and properties of the step, through the C ABI, checked
+against the CPU oracle or against properties that need no oracle."""
+import numpy as np
+import pytest
+
+from oracle import bsgd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+OPTS = {
+    "sgd": dict(opt="sgd", lr=0.1, momentum=0.0, decay=0.0, eps=0.0, clip_norm=0.0),
+    "momentum": dict(opt="momentum", lr=0.05, momentum=0.9, decay=0.0, eps=0.0, clip_norm=0.0),
+    "rmsprop_mom": dict(opt="rmsprop_mom", lr=0.045, momentum=0.9, decay=0.9, eps=1e-3, clip_norm=0.0),
+}
+NS = {"sgd": 0, "momentum": 1, "rmsprop_mom": 2}
+
+
+def _f32(h):
+    return {k: (v if k == "opt" else float(np.float32(v))) for k, v in h.items()}
+
+
+class Case:
+    """A small ad-hoc problem living on the GPU, with a matching fp64 oracle copy.
+
+    layout: list of (grad_offset, numel); theta_shift: element offset of every
+    tensor's theta/state view inside its own allocation (to misalign them)."""
+
+    def __init__(self, N, b, layout, opt, seed=0, ld=None, theta_shift=0, hyper=None):
+        import torch
+        import paper_1604_00981_amd as bs
+        self.bs, self.torch = bs, torch
+        self.N, self.b, self.W = N, b, N + b
+        self.layout, self.opt = layout, opt
+        self.hy = _f32(dict(OPTS[opt], **(hyper or {})))
+        r = np.random.default_rng(seed)
+        self.r = r
+        span = max([o + n for o, n in layout] + [0])
+        self.span = span
+        self.ld = ((span + 3) // 4 * 4) if ld is None else ld
+        ns = NS[opt]
+        self.th, self.s = [], [[] for _ in range(ns)]
+        self.otz = []
+        for o, n in layout:
+            t0 = (r.standard_normal(n) * 0.05).astype(np.float32)
+            buf = torch.zeros(n + theta_shift, device="cuda")
+            buf[theta_shift:] = torch.from_numpy(t0).cuda()
+            self.th.append(buf[theta_shift:])
+            for i in range(ns):
+                self.s[i].append(torch.zeros(n + theta_shift, device="cuda")[theta_shift:])
+            self.otz.append(dict(theta=t0.astype(np.float64), s0=np.zeros(n) if ns > 0 else None,
+                                 s1=np.zeros(n) if ns > 1 else None, grad_offset=o))
+        self.tensors = bs.make_tensors([(self.th[j], self.s[0][j] if ns > 0 else None,
+                                         self.s[1][j] if ns > 1 else None, o, n)
+                                        for j, (o, n) in enumerate(layout)])
+        self.hyper = bs.make_hyper(**self.hy)
+        self.ws = bs.alloc_workspace(span, N, b, len(layout), self.hyper)
+
+    def draw(self, sigma=0.01):
+        g = np.zeros((self.W, self.ld), np.float32)
+        g[:, :self.span] = (self.r.standard_normal((self.W, self.span)) * sigma).astype(np.float32)
+        t = (1.0 + self.r.exponential(1.0, self.W)).astype(np.float32)
+        return g, t
+
+    def gpu_step(self, g, t):
+        torch, bs = self.torch, self.bs
+        self.g_dev = torch.from_numpy(g).cuda()
+        bs.bsgd_step(self.g_dev, self.ld, torch.from_numpy(t).cuda(), self.N, self.b, self.tensors, self.hyper, self.ws)
+        return bs.bsgd_last_status(self.ws)
+
+    def both(self, g, t):
+        status, t_step = self.gpu_step(g, t)
+        ok, sel, ots = orc.step(g, t, self.N, self.b, self.otz, self.hy)
+        assert (status == 0) == ok
+        if ok:
+            assert self.bs.bsgd_last_selection(self.ws, self.N) == sel.tolist()
+            assert np.float32(t_step) == ots
+        return status
+
+    def gpu_arrays(self):
+        out = {"theta": np.concatenate([x.cpu().numpy() for x in self.th]) if self.th else np.zeros(0)}
+        for i, nm in enumerate(("s0", "s1")[:len(self.s)]):
+            out[nm] = np.concatenate([x.cpu().numpy() for x in self.s[i]])
+        return out
+
+    def compare(self, tol=1e-6):
+        got = self.gpu_arrays()
+        for nm, arr in got.items():
+            ref = np.concatenate([t[nm] for t in self.otz])
+            den = np.linalg.norm(ref)
+            rel = np.linalg.norm(arr.astype(np.float64) - ref) / (den if den > 0 else 1.0)
+            assert rel <= tol, (nm, rel)
+            # element-wise too: nothing may be left un-updated at a tensor edge
+            np.testing.assert_allclose(arr, ref, rtol=2e-5, atol=1e-7, err_msg=nm)
+
+
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "rmsprop_mom"])
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 255, 1023, 1024, 1025, 2047, 4096, 4097, 8191, 12289])
+def test_ragged_sizes_single_tensor(opt, P):
+    c = Case(5, 2, [(0, P)], opt, seed=P)
+    for _ in range(2):
+        c.both(*c.draw())
+    c.compare()
+
+
+@pytest.mark.parametrize("opt", ["sgd", "rmsprop_mom"])
+@pytest.mark.parametrize("shift", [0, 1, 2, 3])
+@pytest.mark.parametrize("goff", [0, 1, 2, 3, 5])
+def test_misaligned_tensor_starts(opt, shift, goff):
+    # theta/state start `shift` elements into their allocation, the gradient
+    # segment starts `goff` elements into the row: every relative phase occurs
+    layout = [(goff, 3001), (goff + 3001, 1), (goff + 3002, 2050), (goff + 5052 + 3, 77)]   # a gap of 3 too
+    c = Case(4, 1, layout, opt, seed=10 * shift + goff, theta_shift=shift)
+    for _ in range(2):
+        c.both(*c.draw())
+    c.compare()
+
+
+def test_many_tensors_multiple_upload_batches_and_empty_ones():
+    r = np.random.default_rng(5)
+    sizes = [int(x) for x in r.integers(0, 700, 333)]          # some are empty
+    sizes[0], sizes[-1], sizes[100] = 0, 0, 9000
+    layout, o = [], 0
+    for n in sizes:
+        layout.append((o, n))
+        o += n
+    c = Case(6, 2, layout, "rmsprop_mom", seed=6)
+    for _ in range(2):
+        c.both(*c.draw())
+    c.compare()
+
+
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "rmsprop_mom"])
+def test_clipped_step_matches_oracle_multi_tensor(opt):
+    layout = [(0, 5000), (5000, 3), (5003, 1200), (6203, 4097)]
+    c = Case(7, 2, layout, opt, seed=3, hyper=dict(clip_norm=0.01))
+    for i in range(3):
+        g, t = c.draw(sigma=0.01)
+        c.both(g, t)
+        nrm, scale = c.bs.bsgd_last_clip(c.ws)
+        sel, _ = orc.select_first_n(t, c.N, c.b)
+        G = [orc.reduce_mean(g, sel, o, o + n) for o, n in layout]
+        ref_nrm = float(np.sqrt(sum(np.dot(x, x) for x in G)))
+        assert nrm == pytest.approx(ref_nrm, rel=1e-6)
+        assert scale == pytest.approx(orc.clip_scale(G, c.hy["clip_norm"]), rel=1e-6)
+        assert scale < 1.0
+    c.compare()
+
+
+def test_clip_threshold_above_norm_changes_nothing():
+    layout = [(0, 3000)]
+    a = Case(4, 1, layout, "momentum", seed=8)
+    b = Case(4, 1, layout, "momentum", seed=8, hyper=dict(clip_norm=1e6))
+    for _ in range(2):
+        g, t = a.draw()
+        b.r = a.r
+        a.gpu_step(g, t)
+        b.gpu_step(g, t)
+        nrm, scale = b.bs.bsgd_last_clip(b.ws)
+        assert scale == 1.0
+    ga, gb = a.gpu_arrays(), b.gpu_arrays()
+    for k in ga:
+        assert np.array_equal(ga[k], gb[k])
+
+
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "rmsprop_mom"])
+def test_too_few_arrivals_leaves_theta_and_state_untouched(opt):
+    c = Case(4, 2, [(0, 5000), (5000, 1501)], opt, seed=11)
+    g, t = c.draw()
+    assert c.both(g, t) == 0
+    before = c.gpu_arrays()
+    t_bad = t.copy()
+    t_bad[[0, 2, 5]] = [np.inf, np.nan, np.inf]                # only 3 of 6 arrive, N = 4
+    assert c.both(g, t_bad) == c.bs.BSGD_ERR_TOO_FEW
+    after = c.gpu_arrays()
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k
+    # and with clipping on (three kernels must all stand down)
+    cc = Case(4, 2, [(0, 5000)], opt, seed=12, hyper=dict(clip_norm=0.001))
+    g, t = cc.draw()
+    cc.both(g, t)
+    before = cc.gpu_arrays()
+    assert cc.both(g, t_bad) == cc.bs.BSGD_ERR_TOO_FEW
+    after = cc.gpu_arrays()
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k
+    # the next good step works again
+    assert cc.both(*cc.draw()) == 0
+    cc.compare()
+
+
+@pytest.mark.parametrize("opt", ["sgd", "rmsprop_mom"])
+def test_dropped_rows_are_never_read(opt):
+    # NaN in dropped rows must not reach theta: bitwise equal to zero-filled rows
+    a = Case(5, 3, [(0, 9001)], opt, seed=13)
+    b = Case(5, 3, [(0, 9001)], opt, seed=13)
+    for _ in range(2):
+        g, t = a.draw()
+        b.r = a.r
+        sel, _ = orc.select_first_n(t, 5, 3)
+        dropped = [k for k in range(8) if k not in set(sel.tolist())]
+        g_nan, g_zero = g.copy(), g.copy()
+        g_nan[dropped] = np.nan
+        g_zero[dropped] = 0.0
+        a.gpu_step(g_nan, t)
+        b.gpu_step(g_zero, t)
+    ga, gb = a.gpu_arrays(), b.gpu_arrays()
+    for k in ga:
+        assert np.isfinite(ga[k]).all()
+        assert np.array_equal(ga[k], gb[k]), k
+
+
+def test_worker_permutation():
+    N, b, P = 9, 4, 6001
+    a = Case(N, b, [(0, P)], "momentum", seed=14)
+    p = Case(N, b, [(0, P)], "momentum", seed=14)
+    g, t = a.draw()
+    perm = np.random.default_rng(1).permutation(N + b)
+    a.gpu_step(g, t)
+    p.gpu_step(np.ascontiguousarray(g[perm]), np.ascontiguousarray(t[perm]))
+    sel_a = a.bs.bsgd_last_selection(a.ws, N)
+    sel_p = p.bs.bsgd_last_selection(p.ws, N)
+    assert sorted(int(perm[j]) for j in sel_p) == sel_a
+    ga, gp = a.gpu_arrays(), p.gpu_arrays()
+    # same set, different summation order: equal up to fp32 rounding of the sum
+    np.testing.assert_allclose(gp["theta"], ga["theta"], rtol=1e-6, atol=1e-9)
+
+
+def test_b0_keeps_everyone_and_equals_plain_mean_update():
+    c = Case(6, 0, [(0, 4099)], "sgd", seed=15)
+    g, t = c.draw()
+    th0 = c.gpu_arrays()["theta"].astype(np.float64)
+    c.gpu_step(g, t)
+    assert c.bs.bsgd_last_selection(c.ws, 6) == list(range(6))
+    ref = th0 - c.hy["lr"] * g[:, :4099].astype(np.float64).mean(axis=0)
+    np.testing.assert_allclose(c.gpu_arrays()["theta"], ref, rtol=1e-6, atol=1e-9)
+
+
+def test_run_to_run_determinism_and_checkpoint_resume():
+    def run(split_at=None):
+        c = Case(10, 3, [(1, 7001), (7002, 333)], "rmsprop_mom", seed=16)
+        for i in range(6):
+            g, t = c.draw()
+            if split_at is not None and i == split_at:
+                # checkpoint: copy everything out, into fresh buffers, and go on
+                snap = c.gpu_arrays()
+                c2 = Case(10, 3, [(1, 7001), (7002, 333)], "rmsprop_mom", seed=99)
+                o = 0
+                for j, (_, n) in enumerate(c.layout):
+                    c2.th[j].copy_(c.torch.from_numpy(snap["theta"][o:o + n]))
+                    c2.s[0][j].copy_(c.torch.from_numpy(snap["s0"][o:o + n]))
+                    c2.s[1][j].copy_(c.torch.from_numpy(snap["s1"][o:o + n]))
+                    o += n
+                c2.r = c.r
+                c = c2
+            c.gpu_step(g, t)
+        return c.gpu_arrays()
+
+    a, b, r = run(), run(), run(split_at=3)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k            # bitwise repeatable
+        assert np.array_equal(a[k], r[k]), k            # state is entirely caller-owned
+
+
+def test_every_compiled_launch_shape_gives_identical_bits():
+    import paper_1604_00981_amd as bs
+    shapes = [(1, 16, 1), (1, 8, 1), (2, 8, 1), (2, 16, 1), (4, 4, 1), (4, 8, 1), (1, 16, 0), (2, 8, 0)]
+    results = []
+    try:
+        for vec, unroll, nt in shapes:
+            bs.bsgd_set_tuning(vec, unroll, nt)
+            c = Case(23, 3, [(2, 20011), (20013, 5), (20018, 4100)], "rmsprop_mom", seed=17, hyper=dict(clip_norm=0.0))
+            for _ in range(2):
+                c.gpu_step(*c.draw())
+            cc = Case(23, 3, [(2, 20011), (20013, 5), (20018, 4100)], "momentum", seed=18, hyper=dict(clip_norm=0.002))
+            for _ in range(2):
+                cc.gpu_step(*cc.draw())
+            results.append((c.gpu_arrays(), cc.gpu_arrays()))
+    finally:
+        bs.bsgd_set_tuning(*shapes[0])
+    for (a, ac), (b, bc) in zip(results, results[1:]):
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k        # rows are added in the same order in every shape
+        # the clipped norm is summed per block, so block shape may move its last bits
+        for k in ac:
+            np.testing.assert_allclose(ac[k], bc[k], rtol=1e-6, atol=1e-9)
+
+
+def test_async_server_case_N1_b0():
+    # Algorithm 2's server: apply the one gradient that arrived
+    c = Case(1, 0, [(0, 1030)], "sgd", seed=19)
+    g, t = c.draw()
+    th0 = c.gpu_arrays()["theta"]
+    c.gpu_step(g, t)
+    ref = th0 - np.float32(c.hy["lr"]) * g[0, :1030]
+    np.testing.assert_allclose(c.gpu_arrays()["theta"], ref, rtol=1e-6, atol=1e-9)
+
+
+def test_max_workers():
+    c = Case(250, 6, [(0, 2051)], "momentum", seed=20)
+    c.both(*c.draw())
+    c.compare()
