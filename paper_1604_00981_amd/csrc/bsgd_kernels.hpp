@@ -197,16 +197,19 @@ __device__ __forceinline__ void sum_rows(f4 (&acc)[V], const float* __restrict__
 
 // The optimizer update of one element; g is the (mean, possibly clipped)
 // aggregated gradient.
+// The library is compiled with floating-point contraction off and spells its
+// fused multiply-adds out, so an element gets the same bits whichever path
+// (vector or edge) and launch shape handles it.
 template <int MODE>
 __device__ __forceinline__ void update_elem(float g, float& th, float& a, float& b, const StepParams& p) {
   if constexpr (MODE == kSgd) {
-    th = th - p.lr * g;
+    th = fmaf(-p.lr, g, th);
   } else if constexpr (MODE == kMomentum) {
-    a = p.mu * a + g;
-    th = th - p.lr * a;
+    a = fmaf(p.mu, a, g);
+    th = fmaf(-p.lr, a, th);
   } else if constexpr (MODE == kRmspropMom) {
-    a = p.rho * a + p.one_minus_rho * (g * g);
-    b = p.mu * b + p.lr * g / sqrtf(a + p.eps);
+    a = fmaf(p.rho, a, p.one_minus_rho * (g * g));
+    b = fmaf(p.mu, b, (p.lr * g) / sqrtf(a + p.eps));
     th = th - b;
   }
 }
@@ -328,7 +331,10 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         *reinterpret_cast<f4*>(reinterpret_cast<char*>(p.gbar + colbase) + toff[v]) = g[v];
-        sumsq += g[v].x * g[v].x + g[v].y * g[v].y + g[v].z * g[v].z + g[v].w * g[v].w;
+        sumsq = fmaf(g[v].x, g[v].x, sumsq);
+        sumsq = fmaf(g[v].y, g[v].y, sumsq);
+        sumsq = fmaf(g[v].z, g[v].z, sumsq);
+        sumsq = fmaf(g[v].w, g[v].w, sumsq);
       }
     } else {
 #pragma unroll
@@ -376,7 +382,7 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
         const long long e = e0 + q;
         if constexpr (MODE == kClipReduce) {
           p.gbar[col + q] = gv[q];
-          sumsq += gv[q] * gv[q];
+          sumsq = fmaf(gv[q], gv[q], sumsq);
         } else {
           float th = tz.theta[e], a = 0.f, b = 0.f;
           if constexpr (MODE >= kMomentum) a = tz.s0[e];
