@@ -42,7 +42,7 @@ def cpu_baseline(cfg, seconds_target: float = 15.0):
     import workloads as wl
     from oracle import bsgd_oracle as orc
 
-    blocks = list(range(8))                                   # 8 x 65536 columns
+    blocks = list(range(32))                                  # 32 x 65536 columns
     n = sum(min(wl.BLOCK, cfg.P - b * wl.BLOCK) for b in blocks)
     g = wl.grad_columns(cfg, 0, blocks)
     hy = dict(opt=cfg.opt, lr=cfg.lr, momentum=cfg.momentum, decay=cfg.decay, eps=cfg.eps, clip_norm=0.0)
@@ -55,7 +55,7 @@ def cpu_baseline(cfg, seconds_target: float = 15.0):
         orc.step(g, wl.arrival_times(cfg, reps + 1), cfg.N, cfg.b, tz, hy)
         reps += 1
         dt = time.perf_counter() - t0
-        if dt >= seconds_target or reps >= 200:
+        if dt >= seconds_target or reps >= 400:
             break
     per_step_sample = dt / reps
     gbs = required_bytes(cfg.N, n, cfg.opt) / per_step_sample / 1e9
@@ -86,7 +86,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2", help="workload (C2 is the headline; others for exploration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tuning", default="", help="vec,unroll,nontemporal override for the reduce kernel")
+    ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
+                    help="also run plain device copies of this many MiB (yardstick for the profiler's HBM counters)")
+    ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal,map override for the reduce kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the step shards along P across GPUs by design, "
@@ -162,6 +164,15 @@ def main() -> int:
         kb[i].record(stream)
     torch.cuda.synchronize()
     kernel_ms = sum(a.elapsed_time(c) for a, c in zip(ka, kb)) / K
+
+    if args.calibration_copy > 0:
+        nb = args.calibration_copy << 20
+        src = torch.ones(nb // 4, device="cuda")
+        dst = torch.zeros(nb // 4, device="cuda")
+        for _ in range(3):
+            bs.bsgd_calibration_copy(dst, src, nb)
+        torch.cuda.synchronize()
+        del src, dst
 
     req = required_bytes(N, P, cfg.opt)
     gbs = req / (ms_per_step * 1e-3) / 1e9

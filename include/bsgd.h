@@ -99,8 +99,10 @@ int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b,
  * take the mean, optionally clip, apply one optimizer update to every tensor.
  *
  *   grads     DEVICE fp32[(N+b) x ld], row k = worker k's gradient; only rows
- *             listed in sel_idx are read.  Must not alias theta/state.
- *   ld        row stride in elements, >= every grad_offset + numel.
+ *             listed in sel_idx are read.  16-byte aligned.  Must not alias
+ *             theta/state.
+ *   ld        row stride in elements, a multiple of 4, >= every
+ *             grad_offset + numel (pad the stride to stagger rows if wanted).
  *   sel_idx   DEVICE int32[N] (as written by bsgd_select_first_n), values in [0, N+b).
  *   status    DEVICE int32 or NULL: when non-NULL and the word is non-zero at
  *             execution time the kernels do nothing.
@@ -146,12 +148,30 @@ int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t*
  * workspace.  HOST out pointers, either may be NULL. */
 int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float* scale_out);
 
-/* Launch-shape tuning for the reduce/update kernel, process-wide; for
- * benchmarking.  vec = float4 columns per thread (1, 2 or 4), unroll = rows
- * in flight per batch (4, 8 or 16), nontemporal = 0/1 streaming loads of the
- * gradient rows.  A value of -1 keeps the built-in choice.  Returns
- * BSGD_ERR_ARG for a combination that is not compiled in. */
-int bsgd_set_tuning(int32_t vec, int32_t unroll, int32_t nontemporal);
+/* Launch shape of the reduce/update kernel, process-wide; for benchmarking.
+ * A shape is (block, vec, unroll, nontemporal, map):
+ *   block        threads per workgroup
+ *   vec          float4 columns per thread
+ *   unroll       kept rows loaded per batch before the first add
+ *   nontemporal  0/1: gradient rows are loaded with the streaming hint
+ *   map          0: workgroup-strided columns, 1: each wavefront reads one
+ *                contiguous piece of a row
+ * Every shape adds the kept rows in the same order, so results do not depend
+ * on it.  By default the library picks a shape from the problem size (the
+ * widest chunk that still fills every compute unit several times over).
+ * bsgd_set_tuning pins a compiled-in shape (-1 keeps a field of the current
+ * one; all five -1 returns to the automatic choice) and returns BSGD_ERR_ARG
+ * when that combination is not compiled in; bsgd_num_shapes / bsgd_get_shape
+ * enumerate them (out5 is HOST int32[5] in the order above). */
+int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal, int32_t map);
+int bsgd_num_shapes(void);
+int bsgd_get_shape(int32_t i, int32_t* out5);
+
+/* Measurement aid, not part of the step: a plain device-to-device copy of
+ * `bytes` bytes (a multiple of 16; both pointers DEVICE, 16-byte aligned,
+ * not overlapping).  It reads and writes exactly `bytes` bytes of HBM, which
+ * makes it the yardstick hardware traffic counters are scaled against. */
+int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
 /* Human-readable text for a BSGD_* code. */
 const char* bsgd_strerror(int code);

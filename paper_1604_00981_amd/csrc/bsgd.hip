@@ -7,6 +7,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 using namespace bsgd;
@@ -28,9 +29,51 @@ struct WsLayout {
   long long max_chunks;
 };
 
-constexpr int kMinChunkElems = 4 * kBlock;            // V = 1
-
 bool clip_on(const bsgd_hyper* h) { return h && h->clip_norm > 0.0f && std::isfinite(h->clip_norm); }
+
+// ---------------------------------------------------------------------------
+// kernel variants (launch shapes)
+// ---------------------------------------------------------------------------
+using StepKernel = void (*)(StepParams);
+
+struct Variant {
+  int BS, V, U, NT, MAP;
+  StepKernel rows[4][2];     // [mode incl. clip-reduce][multi]   gradient from the kept rows
+  StepKernel apply[3][2];    // [mode][multi]                      gradient from the stored mean
+};
+
+#define BSGD_SHAPE(BS, V, U, NT, MAP) Shape<BS, V, U, (NT) != 0, MAP>
+#define BSGD_VARIANT(BS, V, U, NT, MAP)                                                                      \
+  {BS, V, U, NT, MAP,                                                                                        \
+   {{k_step<kSgd, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kSgd, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>},               \
+    {k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>},     \
+    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>}, \
+    {k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>}}, \
+   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>},               \
+    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>},     \
+    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>}}}
+
+// Ordered widest chunk first (the automatic choice walks it in order).  A
+// build may supply its own list.
+#ifndef BSGD_VARIANT_LIST
+#define BSGD_VARIANT_LIST                                                                      \
+  BSGD_VARIANT(256, 8, 2, 1, 0), BSGD_VARIANT(256, 4, 2, 1, 0), BSGD_VARIANT(256, 2, 4, 1, 0), \
+  BSGD_VARIANT(256, 1, 8, 1, 0), BSGD_VARIANT(256, 8, 2, 0, 0)
+#endif
+
+const Variant kVariants[] = {BSGD_VARIANT_LIST};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+// Smallest chunk (in elements) over the compiled shapes: bounds the number of
+// workgroups, hence the size of the per-block partial-sum array.
+long long min_chunk_elems() {
+  long long m = 1LL << 40;
+  for (const Variant& v : kVariants) {
+    const long long e = 4LL * v.BS * v.V;
+    if (e < m) m = e;
+  }
+  return m;
+}
 
 WsLayout layout(long long span, int T, bool clip) {
   WsLayout L{};
@@ -39,7 +82,7 @@ WsLayout layout(long long span, int T, bool clip) {
   L.cb_off = L.table_off + round_up(sizeof(DevTensor) * (size_t)T, kAlign);
   L.partials_off = L.cb_off + round_up(sizeof(int) * ((size_t)T + 1), kAlign);
   // every tensor adds at most two partly filled chunks on top of span/chunk
-  L.max_chunks = span / kMinChunkElems + 2LL * T + 2;
+  L.max_chunks = span / min_chunk_elems() + 2LL * T + 2;
   L.gbar_off = L.partials_off;
   L.total = L.partials_off;
   if (clip) {
@@ -49,53 +92,41 @@ WsLayout layout(long long span, int T, bool clip) {
   return L;
 }
 
-// ---------------------------------------------------------------------------
-// kernel variants
-// ---------------------------------------------------------------------------
-using StepKernel = void (*)(StepParams);
+std::atomic<int> g_variant{-1};                      // -1: choose by problem size
 
-struct Variant {
-  int V, U, NT;
-  StepKernel rows[4][2];     // [mode][multi]
-};
-
-#define BSGD_ROWS(V, U, NT)                                                                            \
-  {V, U, NT,                                                                                           \
-   {{k_step<kSgd, V, U, NT != 0, false, true>, k_step<kSgd, V, U, NT != 0, true, true>},               \
-    {k_step<kMomentum, V, U, NT != 0, false, true>, k_step<kMomentum, V, U, NT != 0, true, true>},     \
-    {k_step<kRmspropMom, V, U, NT != 0, false, true>, k_step<kRmspropMom, V, U, NT != 0, true, true>}, \
-    {k_step<kClipReduce, V, U, NT != 0, false, true>, k_step<kClipReduce, V, U, NT != 0, true, true>}}}
-
-const Variant kVariants[] = {
-    BSGD_ROWS(1, 16, 1), BSGD_ROWS(1, 8, 1), BSGD_ROWS(2, 8, 1), BSGD_ROWS(2, 16, 1),
-    BSGD_ROWS(4, 4, 1),  BSGD_ROWS(4, 8, 1), BSGD_ROWS(1, 16, 0), BSGD_ROWS(2, 8, 0),
-};
-constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-
-struct ApplyVariant {
-  int V;
-  StepKernel apply[3][2];    // [mode][multi]
-};
-#define BSGD_APPLY(V)                                                                              \
-  {V,                                                                                              \
-   {{k_step<kSgd, V, 1, false, false, false>, k_step<kSgd, V, 1, false, true, false>},             \
-    {k_step<kMomentum, V, 1, false, false, false>, k_step<kMomentum, V, 1, false, true, false>},   \
-    {k_step<kRmspropMom, V, 1, false, false, false>, k_step<kRmspropMom, V, 1, false, true, false>}}}
-const ApplyVariant kApply[] = {BSGD_APPLY(1), BSGD_APPLY(2), BSGD_APPLY(4)};
-
-std::atomic<int> g_variant{0};
-
-const ApplyVariant* apply_for(int V) {
-  for (const ApplyVariant& a : kApply)
-    if (a.V == V) return &a;
-  return nullptr;
+// Automatic choice: the table is ordered widest chunk first; take the first
+// shape that still yields enough workgroups to fill every CU several times.
+int compute_units() {
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    return n;
+  }();
+  return cus;
 }
 
-int launch(StepKernel fn, long long grid, size_t lds, hipStream_t stream, StepParams& p) {
+const Variant& pick_variant(long long total_groups) {
+  const int forced = g_variant.load(std::memory_order_relaxed);
+  if (forced >= 0) return kVariants[forced];
+  const long long want = 4LL * compute_units();
+  for (const Variant& v : kVariants) {
+    if (!v.NT) continue;                               // plain-load shapes are for comparison only
+    if (total_groups / ((long long)v.BS * v.V) >= want) return v;
+  }
+  int best = 0;
+  for (int i = 1; i < kNumVariants; ++i)
+    if ((long long)kVariants[i].BS * kVariants[i].V < (long long)kVariants[best].BS * kVariants[best].V) best = i;
+  return kVariants[best];
+}
+
+int launch(StepKernel fn, int block, long long grid, size_t lds, hipStream_t stream, StepParams& p) {
   if (grid <= 0) return BSGD_OK;
-  if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
+  if (grid > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   void* args[] = {&p};
-  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(kBlock), args, lds, stream);
+  static const size_t lds_pad = [] { const char* e = getenv("BSGD_LDS_PAD"); return e ? (size_t)atol(e) : (size_t)0; }();
+  lds += lds_pad;                                    // experiment knob: throttles workgroups per CU
+  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(block), args, lds, stream);
   return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 
@@ -149,7 +180,7 @@ static int validate_update_args(const float* grads, int64_t ld, int32_t N, const
   const WsLayout L = layout(span, T, clip_on(hyper));
   if (workspace_bytes < L.total) return BSGD_ERR_ARG;
   // chunk ids are 32-bit
-  if (span / kMinChunkElems + 2LL * T + 2 > 0x7fffffffLL) return BSGD_ERR_ARG;
+  if (L.max_chunks > 0x7fffffffLL) return BSGD_ERR_ARG;
   *span_out = span;
   return BSGD_OK;
 }
@@ -161,9 +192,9 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   const bool clip = clip_on(hyper);
   const WsLayout L = layout(span, T, clip);
   char* ws = static_cast<char*>(workspace);
-  const Variant& var = kVariants[g_variant.load(std::memory_order_relaxed)];
+  const Variant& var = pick_variant((span + 3) / 4);
   const int V = var.V;
-  const long long chunk_groups = (long long)kBlock * V;
+  const long long chunk_groups = (long long)var.BS * V;
 
   StepParams p{};
   p.grads = grads;
@@ -218,16 +249,14 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
     lds = sizeof(int) * ((size_t)T + 1);
   }
 
-  if (!clip) return launch(var.rows[mode][multi ? 1 : 0], total_chunks, lds, stream, p);
+  if (!clip) return launch(var.rows[mode][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
 
-  int rc = launch(var.rows[kClipReduce][multi ? 1 : 0], total_chunks, lds, stream, p);
+  int rc = launch(var.rows[kClipReduce][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
-  const ApplyVariant* av = apply_for(V);
-  if (av == nullptr) return BSGD_ERR_ARG;
-  return launch(av->apply[mode][multi ? 1 : 0], total_chunks, lds, stream, p);
+  return launch(var.apply[mode][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
@@ -284,16 +313,43 @@ int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float*
   return BSGD_OK;
 }
 
-int bsgd_set_tuning(int32_t vec, int32_t unroll, int32_t nontemporal) {
-  const Variant& cur = kVariants[g_variant.load(std::memory_order_relaxed)];
-  const int V = vec < 0 ? cur.V : vec, U = unroll < 0 ? cur.U : unroll, NT = nontemporal < 0 ? cur.NT : nontemporal;
+int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal, int32_t map) {
+  if (block < 0 && vec < 0 && unroll < 0 && nontemporal < 0 && map < 0) {
+    g_variant.store(-1, std::memory_order_relaxed);    // back to the automatic choice
+    return BSGD_OK;
+  }
+  const int cur_i = g_variant.load(std::memory_order_relaxed);
+  const Variant& cur = kVariants[cur_i < 0 ? 0 : cur_i];
+  const int BS = block < 0 ? cur.BS : block, V = vec < 0 ? cur.V : vec, U = unroll < 0 ? cur.U : unroll;
+  const int NT = nontemporal < 0 ? cur.NT : nontemporal, MAP = map < 0 ? cur.MAP : map;
   for (int i = 0; i < kNumVariants; ++i) {
-    if (kVariants[i].V == V && kVariants[i].U == U && kVariants[i].NT == NT) {
+    const Variant& v = kVariants[i];
+    if (v.BS == BS && v.V == V && v.U == U && v.NT == NT && v.MAP == MAP) {
       g_variant.store(i, std::memory_order_relaxed);
       return BSGD_OK;
     }
   }
   return BSGD_ERR_ARG;
+}
+
+int bsgd_num_shapes(void) { return kNumVariants; }
+
+int bsgd_get_shape(int32_t i, int32_t* out5) {
+  if (i < 0 || i >= kNumVariants || out5 == nullptr) return BSGD_ERR_ARG;
+  const Variant& v = kVariants[i];
+  out5[0] = v.BS; out5[1] = v.V; out5[2] = v.U; out5[3] = v.NT; out5[4] = v.MAP;
+  return BSGD_OK;
+}
+
+int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+  if (dst == nullptr || src == nullptr || bytes <= 0 || (bytes & 15) != 0) return BSGD_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0 || (reinterpret_cast<uintptr_t>(src) & 15) != 0) return BSGD_ERR_ARG;
+  const long long n16 = bytes / 16;
+  const long long grid = (n16 + 255) / 256;
+  if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
+  hipLaunchKernelGGL(k_calibration_copy, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const f4*>(src), static_cast<f4*>(dst), n16);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 
 const char* bsgd_strerror(int code) {

@@ -20,7 +20,23 @@ namespace bsgd {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef f4 f4u __attribute__((aligned(4)));          // float4 that is only 4-byte aligned
 
-constexpr int kBlock = 256;                           // threads per workgroup (4 wavefronts)
+// Launch shape of the reduce/update kernel.
+//   BS   threads per workgroup
+//   V    float4 columns per thread (a chunk is BS*V float4 groups wide)
+//   U    kept rows loaded per batch before the first add
+//   NT   gradient rows are loaded with the non-temporal (streaming) hint
+//   MAP  0: thread t takes groups t, t+BS, ...   (workgroup-strided)
+//        1: wave w takes V*64 consecutive groups (each wavefront reads one
+//           contiguous V KiB piece of a row)
+template <int BS_, int V_, int U_, bool NT_, int MAP_>
+struct Shape {
+  static constexpr int BS = BS_, V = V_, U = U_, MAP = MAP_;
+  static constexpr bool NT = NT_;
+  __device__ static __forceinline__ int group_of(int v) {
+    if constexpr (MAP_ == 0) return v * BS_ + (int)threadIdx.x;
+    else return (((int)threadIdx.x >> 6) * V_ + v) * 64 + ((int)threadIdx.x & 63);
+  }
+};
 constexpr int kMaxWorkers = 256;
 
 enum Mode : int { kSgd = 0, kMomentum = 1, kRmspropMom = 2, kClipReduce = 3 };
@@ -235,15 +251,16 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 // Sum over the workgroup in a fixed order; the result is valid in thread 0.
-__device__ __forceinline__ double block_sum(float x, float* lds4) {
+template <int BS>
+__device__ __forceinline__ double block_sum(float x, float* lds) {
   x = wave_sum(x);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) lds4[wave] = x;
+  if ((threadIdx.x & 63) == 0) lds[wave] = x;
   __syncthreads();
   double s = 0.0;
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) s += (double)lds4[w];
+    for (int w = 0; w < BS / 64; ++w) s += (double)lds[w];
   }
   return s;
 }
@@ -262,23 +279,25 @@ __device__ __forceinline__ int find_tensor(const int* cb, int T, int c) {
 // directly; MODE kClipReduce stores the mean and a per-block sum of squares).
 // !SRC_ROWS: the gradient is the stored mean times the clip scale (MODE 0..2).
 //
-// Work is cut into chunks of 256*V float4 groups.  Groups are aligned to the
+// Work is cut into chunks of BS*V float4 groups.  Groups are aligned to the
 // gradient row (not to theta): group g of a tensor covers elements
 // [4g-h, 4g-h+4) with h = grad_offset mod 4, so row loads are 16-byte aligned
 // whenever grads and ld are; theta/state accesses may then be only 4-byte
 // aligned.  Chunks fully inside a tensor take the vector path with no
 // per-lane tests; the first and last chunk of a tensor take the edge path.
-template <int MODE, int V, int U, bool NT, bool MULTI, bool SRC_ROWS>
-__global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
+template <int MODE, class S, bool MULTI, bool SRC_ROWS>
+__global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
+  constexpr int BS = S::BS, V = S::V, U = S::U;
+  constexpr bool NT = S::NT;
   extern __shared__ int cb_lds[];                      // MULTI: chunk_begin[T+1]
-  __shared__ float red_lds[kBlock / 64];
+  __shared__ float red_lds[BS / 64];
 
   if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
 
   DevTensor tz;
   int c = blockIdx.x;
   if constexpr (MULTI) {
-    for (int i = threadIdx.x; i <= p.T; i += kBlock) cb_lds[i] = p.chunk_begin[i];
+    for (int i = threadIdx.x; i <= p.T; i += BS) cb_lds[i] = p.chunk_begin[i];
     __syncthreads();
     const int j = __builtin_amdgcn_readfirstlane(find_tensor(cb_lds, p.T, c));   // same in every lane
     c -= __builtin_amdgcn_readfirstlane(cb_lds[j]);
@@ -288,10 +307,10 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
   }
 
   const int h = (int)(tz.grad_offset & 3);
-  const long long group0 = (long long)c * (kBlock * V);
+  const long long group0 = (long long)c * (BS * V);
   const long long e_first = 4 * group0 - h;            // first element this chunk covers (may be < 0)
   const long long colbase = tz.grad_offset + e_first;  // same thing inside a gradient row
-  const bool interior = (e_first >= 0) && (e_first + 4LL * kBlock * V <= tz.numel);
+  const bool interior = (e_first >= 0) && (e_first + 4LL * BS * V <= tz.numel);
 
   float scale = 1.0f;
   if constexpr (!SRC_ROWS) scale = p.header->clip_scale;
@@ -301,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
   if (interior) {
     unsigned toff[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) toff[v] = (unsigned)(v * kBlock + threadIdx.x) * 16u;
+    for (int v = 0; v < V; ++v) toff[v] = (unsigned)S::group_of(v) * 16u;
 
     // issue the parameter/state loads first so they overlap the row loop
     f4 th[V], a[V], b[V];
@@ -349,7 +368,7 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
     // Edge chunk: per float4 group, a full group still uses one 16-byte load
     // per row; a group cut by the tensor's start or end goes element by element.
     for (int v = 0; v < V; ++v) {
-      const long long e0 = e_first + 4LL * (v * kBlock + threadIdx.x);
+      const long long e0 = e_first + 4LL * S::group_of(v);
       if (e0 + 4 <= 0 || e0 >= tz.numel) continue;
       const bool full = (e0 >= 0) && (e0 + 4 <= tz.numel);
       float gv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -397,7 +416,7 @@ __global__ __launch_bounds__(kBlock) void k_step(StepParams p) {
   }
 
   if constexpr (MODE == kClipReduce) {
-    const double s = block_sum(sumsq, red_lds);
+    const double s = block_sum<BS>(sumsq, red_lds);
     if (threadIdx.x == 0) p.partials[blockIdx.x] = s;
   }
 }
@@ -423,6 +442,13 @@ __global__ __launch_bounds__(kFinalizeBlock) void k_finalize_norm(const double* 
     header->norm = nrm;
     header->clip_scale = (nrm <= (double)c) ? 1.0f : (float)((double)c / nrm);
   }
+}
+
+// Plain 16-byte-per-thread copy with a known byte count: the yardstick the
+// profiler's HBM read/write counters are scaled against.
+__global__ __launch_bounds__(256) void k_calibration_copy(const f4* __restrict__ src, f4* __restrict__ dst, long long n16) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
 }
 
 }  // namespace bsgd

@@ -265,11 +265,11 @@ def test_run_to_run_determinism_and_checkpoint_resume():
 
 def test_every_compiled_launch_shape_gives_identical_bits():
     import paper_1604_00981_amd as bs
-    shapes = [(1, 16, 1), (1, 8, 1), (2, 8, 1), (2, 16, 1), (4, 4, 1), (4, 8, 1), (1, 16, 0), (2, 8, 0)]
+    shapes = [bs.bsgd_get_shape(i) for i in range(bs.bsgd_num_shapes())]
     results = []
     try:
-        for vec, unroll, nt in shapes:
-            bs.bsgd_set_tuning(vec, unroll, nt)
+        for shape in shapes:
+            bs.bsgd_set_tuning(*shape)
             c = Case(23, 3, [(2, 20011), (20013, 5), (20018, 4100)], "rmsprop_mom", seed=17, hyper=dict(clip_norm=0.0))
             for _ in range(2):
                 c.gpu_step(*c.draw())
@@ -278,7 +278,7 @@ def test_every_compiled_launch_shape_gives_identical_bits():
                 cc.gpu_step(*cc.draw())
             results.append((c.gpu_arrays(), cc.gpu_arrays()))
     finally:
-        bs.bsgd_set_tuning(*shapes[0])
+        bs.bsgd_set_tuning()                          # back to the automatic choice
     for (a, ac), (b, bc) in zip(results, results[1:]):
         for k in a:
             assert np.array_equal(a[k], b[k]), k        # rows are added in the same order in every shape
