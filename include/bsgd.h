@@ -46,7 +46,7 @@ extern "C" {
 #define BSGD_ERR_HIP      (-3)  /* a HIP runtime call failed                        */
 
 #define BSGD_MAX_WORKERS  256   /* N + b may not exceed this                        */
-#define BSGD_MAX_TENSORS  8192  /* T may not exceed this                            */
+#define BSGD_MAX_TENSORS  4096  /* T may not exceed this                            */
 
 /* Which update rule is applied to the aggregated gradient G (Sec. 3:
  * "Sync-Opt"; Sec. 1.1 gives SGD, Appendix A.2/A.3 name RMSProp with
@@ -69,7 +69,9 @@ typedef struct {
 } bsgd_hyper;
 
 /* One parameter tensor.  The struct array itself is HOST memory; the
- * pointers inside are DEVICE pointers, 4-byte aligned, updated in place. */
+ * pointers inside are DEVICE pointers, 4-byte aligned, updated in place.
+ * Tensors may be listed in any order and may leave gaps in the row, but two
+ * tensors may not claim the same gradient columns. */
 typedef struct {
   float*  theta;        /* numel parameters                                         */
   float*  s0;           /* v (BSGD_MOMENTUM) or ms (BSGD_RMSPROP_MOM); else NULL     */
@@ -112,8 +114,8 @@ int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b,
  *
  * Rows are added in ascending worker index in fp32, the sum is multiplied by
  * 1/N once.  Errors: BSGD_ERR_ARG for bad sizes, NULL pointers, a missing
- * state pointer for the chosen optimizer, ld too small or a workspace too
- * small.  Overlap between tensors is not checked. */
+ * state pointer for the chosen optimizer, ld too small, tensors that overlap
+ * in the gradient row, or a workspace too small. */
 int bsgd_reduce_update(const float* grads, int64_t ld,
                        const int32_t* sel_idx, const int32_t* status, int32_t N,
                        const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,

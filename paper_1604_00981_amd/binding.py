@@ -21,7 +21,7 @@ BSGD_ERR_ARG = -1
 BSGD_ERR_TOO_FEW = -2
 BSGD_ERR_HIP = -3
 BSGD_MAX_WORKERS = 256
-BSGD_MAX_TENSORS = 8192
+BSGD_MAX_TENSORS = 4096
 
 BSGD_SGD, BSGD_MOMENTUM, BSGD_RMSPROP_MOM = 0, 1, 2
 _OPT_BY_NAME = {"sgd": BSGD_SGD, "momentum": BSGD_MOMENTUM, "rmsprop_mom": BSGD_RMSPROP_MOM}

@@ -5,10 +5,13 @@
 
 #include "../../include/bsgd.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 using namespace bsgd;
 
@@ -18,14 +21,14 @@ namespace {
 // workspace layout (all offsets multiples of 256 bytes)
 //   [0,256)            WsHeader
 //   [256,1280)         sel_idx int32[256]
-//   then               DevTensor table[T], chunk_begin int32[T+1]
+//   then               Segment table[2T+1], starts uint32[2T+2]  (tensors and the gaps between them)
 //   clipped steps:     partials double[max_chunks], gbar float[span rounded up]
 // ---------------------------------------------------------------------------
 constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-  size_t sel_off, table_off, cb_off, partials_off, gbar_off, total;
+  size_t sel_off, table_off, starts_off, partials_off, gbar_off, total;
   long long max_chunks;
 };
 
@@ -77,12 +80,12 @@ long long min_chunk_elems() {
 
 WsLayout layout(long long span, int T, bool clip) {
   WsLayout L{};
+  const size_t max_segments = 2 * (size_t)T + 1;      // every tensor may be followed by a gap
   L.sel_off = kAlign;
   L.table_off = L.sel_off + round_up(sizeof(int) * kMaxWorkers, kAlign);
-  L.cb_off = L.table_off + round_up(sizeof(DevTensor) * (size_t)T, kAlign);
-  L.partials_off = L.cb_off + round_up(sizeof(int) * ((size_t)T + 1), kAlign);
-  // every tensor adds at most two partly filled chunks on top of span/chunk
-  L.max_chunks = span / min_chunk_elems() + 2LL * T + 2;
+  L.starts_off = L.table_off + round_up(sizeof(Segment) * max_segments, kAlign);
+  L.partials_off = L.starts_off + round_up(sizeof(unsigned) * (max_segments + 1), kAlign);
+  L.max_chunks = span / min_chunk_elems() + 2;
   L.gbar_off = L.partials_off;
   L.total = L.partials_off;
   if (clip) {
@@ -120,14 +123,68 @@ const Variant& pick_variant(long long total_groups) {
   return kVariants[best];
 }
 
-int launch(StepKernel fn, int block, long long grid, size_t lds, hipStream_t stream, StepParams& p) {
-  if (grid <= 0) return BSGD_OK;
-  if (grid > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
-  void* args[] = {&p};
+// How many workgroups of `fn` one launch should hold: as many as are resident
+// on the chip at once (capped at 8 wavefronts per CU, which is enough to
+// saturate HBM).  A launch of exactly one such "round" starts every workgroup
+// at the first kept row at the same moment, so the whole chip walks the rows
+// together and DRAM sees a few long sequential streams; a longer launch lets
+// workgroups drift apart and costs up to 15 % of bandwidth on long rows.
+long long round_size(StepKernel fn, int block, size_t lds) {
+  struct Entry { StepKernel fn; size_t lds; long long n; };
+  static std::mutex mu;
+  static std::vector<Entry> cache;
+  static const int forced_per_cu = [] { const char* e = getenv("BSGD_BLOCKS_PER_CU"); return e ? atoi(e) : 0; }();
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : cache)
+    if (e.fn == fn && e.lds == lds) return e.n;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), block, lds) != hipSuccess || per_cu < 1)
+    per_cu = 1;
+  const int cap = (8 * 64) / block > 0 ? (8 * 64) / block : 1;
+  if (per_cu > cap) per_cu = cap;
+  if (forced_per_cu > 0) per_cu = forced_per_cu;
+  const long long n = (long long)per_cu * compute_units();
+  cache.push_back(Entry{fn, lds, n});
+  return n;
+}
+
+// Enqueue the work on `chunks` chunks as a sequence of near-equal launches of
+// at most one round of workgroups each, one chunk per workgroup.
+// BSGD_LAUNCH_MODE (read once) selects the alternatives kept for comparison:
+// "single" = everything in one launch, "persistent" = one launch of one round
+// of workgroups that stride through the chunk list.
+int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p) {
+  if (chunks <= 0) return BSGD_OK;
+  if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   static const size_t lds_pad = [] { const char* e = getenv("BSGD_LDS_PAD"); return e ? (size_t)atol(e) : (size_t)0; }();
+  static const int mode = [] {
+    const char* e = getenv("BSGD_LAUNCH_MODE");
+    if (e == nullptr) return 1;
+    return strcmp(e, "persistent") == 0 ? 0 : strcmp(e, "single") == 0 ? 2 : 1;
+  }();
   lds += lds_pad;                                    // experiment knob: throttles workgroups per CU
-  hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(block), args, lds, stream);
-  return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+  const long long round = round_size(fn, block, lds);
+  auto go = [&](long long base, long long end, long long grid) -> int {
+    p.chunk_base = (int)base;
+    p.chunk_end = (int)end;
+    void* args[] = {&p};
+    hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(block), args, lds, stream);
+    return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+  };
+  if (mode == 2) return go(0, chunks, chunks);
+  if (mode == 1) {
+    static const int cpb = [] { const char* e = getenv("BSGD_CHUNKS_PER_BLOCK"); return e && atoi(e) > 0 ? atoi(e) : 1; }();
+    const long long cap = round * cpb;               // chunks per launch
+    const long long launches = (chunks + cap - 1) / cap;
+    const long long per = (chunks + launches - 1) / launches;
+    for (long long base = 0; base < chunks; base += per) {
+      const long long n = chunks - base < per ? chunks - base : per;
+      int rc = go(base, base + n, n < round ? n : round);
+      if (rc != BSGD_OK) return rc;
+    }
+    return BSGD_OK;
+  }
+  return go(0, chunks, chunks < round ? chunks : round);
 }
 
 bool check_select_args(const float* arrival_t, int N, int b) {
@@ -153,11 +210,21 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
   return layout(span, T, clip_on(hyper)).total;
 }
 
+// What a call will run on: the tensors as sorted, non-overlapping segments of
+// the gradient row (gaps made explicit), built and checked on the host.
+struct Plan {
+  long long span = 0;                 // largest grad_offset + numel
+  long long col_lo = 0, col_hi = 0;   // columns covered: [col_lo, col_hi)
+  int S = 0;                          // segments (S == 1: `single` is used, the vectors stay empty)
+  Segment single{};
+  std::vector<Segment> segs;
+  std::vector<unsigned> starts;       // S + 1 entries
+};
+
 // Host-only validation shared by bsgd_reduce_update and bsgd_step: nothing is
 // enqueued unless this passes.
-static int validate_update_args(const float* grads, int64_t ld, int32_t N, const bsgd_tensor* tensors, int32_t T,
-                                const bsgd_hyper* hyper, const void* workspace, size_t workspace_bytes,
-                                long long* span_out) {
+static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tensor* tensors, int32_t T,
+                     const bsgd_hyper* hyper, const void* workspace, size_t workspace_bytes, Plan* plan) {
   if (grads == nullptr || tensors == nullptr || hyper == nullptr || workspace == nullptr) return BSGD_ERR_ARG;
   if (N < 1 || N > BSGD_MAX_WORKERS || T < 1 || T > BSGD_MAX_TENSORS || ld < 0) return BSGD_ERR_ARG;
   if (hyper->opt < BSGD_SGD || hyper->opt > BSGD_RMSPROP_MOM) return BSGD_ERR_ARG;
@@ -167,6 +234,7 @@ static int validate_update_args(const float* grads, int64_t ld, int32_t N, const
   if ((reinterpret_cast<uintptr_t>(grads) & 15) != 0 || (ld & 3) != 0) return BSGD_ERR_ARG;
   const int mode = hyper->opt;
   long long span = 0;
+  int live = 0, last_live = -1;
   for (int j = 0; j < T; ++j) {
     const bsgd_tensor& t = tensors[j];
     if (t.numel < 0 || t.grad_offset < 0) return BSGD_ERR_ARG;
@@ -176,25 +244,58 @@ static int validate_update_args(const float* grads, int64_t ld, int32_t N, const
     if (mode == BSGD_RMSPROP_MOM && (t.s1 == nullptr || (reinterpret_cast<uintptr_t>(t.s1) & 3))) return BSGD_ERR_ARG;
     if (t.grad_offset > ld - t.numel) return BSGD_ERR_ARG;
     if (t.grad_offset + t.numel > span) span = t.grad_offset + t.numel;
+    ++live;
+    last_live = j;
   }
+  if (span >= 0xFFFFFFF0LL) return BSGD_ERR_ARG;       // segment starts are kept as 32-bit columns
   const WsLayout L = layout(span, T, clip_on(hyper));
   if (workspace_bytes < L.total) return BSGD_ERR_ARG;
-  // chunk ids are 32-bit
-  if (L.max_chunks > 0x7fffffffLL) return BSGD_ERR_ARG;
-  *span_out = span;
+  plan->span = span;
+  plan->S = 0;
+  if (live == 0) return BSGD_OK;                       // nothing to update
+  if (live == 1) {
+    const bsgd_tensor& t = tensors[last_live];
+    plan->S = 1;
+    plan->single = Segment{t.theta, t.s0, t.s1};
+    plan->col_lo = t.grad_offset;
+    plan->col_hi = t.grad_offset + t.numel;
+    return BSGD_OK;
+  }
+  // sort by position in the row, refuse overlap, make gaps explicit
+  std::vector<int> order;
+  order.reserve(live);
+  for (int j = 0; j < T; ++j)
+    if (tensors[j].numel > 0) order.push_back(j);
+  std::sort(order.begin(), order.end(),
+            [&](int a, int b) { return tensors[a].grad_offset < tensors[b].grad_offset; });
+  plan->segs.reserve(2 * (size_t)live);
+  plan->starts.reserve(2 * (size_t)live + 1);
+  long long at = tensors[order[0]].grad_offset;
+  plan->col_lo = at;
+  for (int idx : order) {
+    const bsgd_tensor& t = tensors[idx];
+    if (t.grad_offset < at) return BSGD_ERR_ARG;       // two tensors claim the same gradient columns
+    if (t.grad_offset > at) {                          // a gap
+      plan->segs.push_back(Segment{nullptr, nullptr, nullptr});
+      plan->starts.push_back((unsigned)at);
+    }
+    plan->segs.push_back(Segment{t.theta, t.s0, t.s1});
+    plan->starts.push_back((unsigned)t.grad_offset);
+    at = t.grad_offset + t.numel;
+  }
+  plan->col_hi = at;
+  plan->starts.push_back((unsigned)at);
+  plan->S = (int)plan->segs.size();
   return BSGD_OK;
 }
 
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
-                          const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
-                          long long span, hipStream_t stream) {
+                          int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream) {
+  if (plan.S == 0) return BSGD_OK;
   const int mode = hyper->opt;
   const bool clip = clip_on(hyper);
-  const WsLayout L = layout(span, T, clip);
+  const WsLayout L = layout(plan.span, T, clip);
   char* ws = static_cast<char*>(workspace);
-  const Variant& var = pick_variant((span + 3) / 4);
-  const int V = var.V;
-  const long long chunk_groups = (long long)var.BS * V;
 
   StepParams p{};
   p.grads = grads;
@@ -211,42 +312,39 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.gbar = reinterpret_cast<float*>(ws + L.gbar_off);
   p.partials = reinterpret_cast<double*>(ws + L.partials_off);
   p.header = reinterpret_cast<const WsHeader*>(ws);
-  p.table = reinterpret_cast<const DevTensor*>(ws + L.table_off);
-  p.chunk_begin = reinterpret_cast<const int*>(ws + L.cb_off);
-  p.T = T;
+  p.table = reinterpret_cast<const Segment*>(ws + L.table_off);
+  p.starts = reinterpret_cast<const unsigned*>(ws + L.starts_off);
+  p.S = plan.S;
+  p.single = plan.single;
+  p.col_lo = plan.col_lo;
+  p.col_hi = plan.col_hi;
+  p.base = plan.col_lo & ~3LL;
 
-  auto chunks_of = [&](const bsgd_tensor& t) -> long long {
-    if (t.numel == 0) return 0;
-    const long long groups = ((t.grad_offset & 3) + t.numel + 3) / 4;
-    return (groups + chunk_groups - 1) / chunk_groups;
-  };
+  const long long cols = ((plan.col_hi + 3) & ~3LL) - p.base;   // columns the chunks must cover
+  const Variant& var = pick_variant(cols / 4);
+  const long long chunk_cols = 4LL * var.BS * var.V;
+  const long long total_chunks = (cols + chunk_cols - 1) / chunk_cols;
+  if (total_chunks > L.max_chunks || total_chunks > 0x7fffffffLL) return BSGD_ERR_ARG;   // cannot happen
 
-  long long total_chunks = 0;
-  const bool multi = T > 1;
+  const bool multi = plan.S > 1;
   size_t lds = 0;
-  if (!multi) {
-    const bsgd_tensor& t = tensors[0];
-    p.single = DevTensor{t.theta, t.s0, t.s1, t.grad_offset, t.numel};
-    total_chunks = chunks_of(t);
-  } else {
-    DevTensor* d_table = reinterpret_cast<DevTensor*>(ws + L.table_off);
-    int* d_cb = reinterpret_cast<int*>(ws + L.cb_off);
-    for (int first = 0; first < T; first += kUploadBatch) {
+  if (multi) {
+    Segment* d_table = reinterpret_cast<Segment*>(ws + L.table_off);
+    unsigned* d_starts = reinterpret_cast<unsigned*>(ws + L.starts_off);
+    for (int first = 0; first < plan.S; first += kUploadBatch) {
       UploadArgs a{};
       a.first = first;
-      a.count = (T - first < kUploadBatch) ? (T - first) : kUploadBatch;
+      a.count = (plan.S - first < kUploadBatch) ? (plan.S - first) : kUploadBatch;
       for (int i = 0; i < a.count; ++i) {
-        const bsgd_tensor& t = tensors[first + i];
-        a.t[i] = DevTensor{t.theta, t.s0, t.s1, t.grad_offset, t.numel};
-        a.chunk_begin[i] = (int)total_chunks;
-        total_chunks += chunks_of(t);
+        a.seg[i] = plan.segs[first + i];
+        a.start[i] = plan.starts[first + i];
       }
-      a.is_last = (first + a.count == T);
-      a.total_chunks = (int)total_chunks;
-      hipLaunchKernelGGL(k_upload_table, dim3(1), dim3(kUploadBatch), 0, stream, a, d_table, d_cb, (int)T);
+      a.is_last = (first + a.count == plan.S);
+      a.end_col = plan.starts[plan.S];
+      hipLaunchKernelGGL(k_upload_table, dim3(1), dim3(kUploadBatch), 0, stream, a, d_table, d_starts, plan.S);
       if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
     }
-    lds = sizeof(int) * ((size_t)T + 1);
+    lds = sizeof(unsigned) * ((size_t)plan.S + 1);
   }
 
   if (!clip) return launch(var.rows[mode][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
@@ -263,25 +361,25 @@ int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, c
                        const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
                        size_t workspace_bytes, void* stream) {
   if (sel_idx == nullptr) return BSGD_ERR_ARG;
-  long long span = 0;
-  int rc = validate_update_args(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &span);
+  Plan plan;
+  int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel_idx, status, N, tensors, T, hyper, workspace, span, (hipStream_t)stream);
+  return enqueue_update(grads, ld, sel_idx, status, N, T, hyper, workspace, plan, (hipStream_t)stream);
 }
 
 int bsgd_step(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
               const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
               size_t workspace_bytes, void* stream) {
   if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
-  long long span = 0;
-  int rc = validate_update_args(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &span);
+  Plan plan;
+  int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
   if (rc != BSGD_OK) return rc;
   char* ws = static_cast<char*>(workspace);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
   int* sel = reinterpret_cast<int*>(ws + kAlign);
   rc = bsgd_select_first_n(arrival_t, N, b, sel, &hdr->t_step, &hdr->status, stream);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel, &hdr->status, N, tensors, T, hyper, workspace, span, (hipStream_t)stream);
+  return enqueue_update(grads, ld, sel, &hdr->status, N, T, hyper, workspace, plan, (hipStream_t)stream);
 }
 
 int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out) {

@@ -33,7 +33,7 @@ struct Shape {
   static constexpr int BS = BS_, V = V_, U = U_, MAP = MAP_;
   static constexpr bool NT = NT_;
   __device__ static __forceinline__ int group_of(int v) {
-    if constexpr (MAP_ == 0) return v * BS_ + (int)threadIdx.x;
+    if constexpr ((MAP_ & 1) == 0) return v * BS_ + (int)threadIdx.x;
     else return (((int)threadIdx.x >> 6) * V_ + v) * 64 + ((int)threadIdx.x & 63);
   }
 };
@@ -41,13 +41,13 @@ constexpr int kMaxWorkers = 256;
 
 enum Mode : int { kSgd = 0, kMomentum = 1, kRmspropMom = 2, kClipReduce = 3 };
 
-// What the host keeps per tensor on the device.
-struct DevTensor {
+// One segment of the gradient row: a parameter tensor (theta != null) or a gap
+// between tensors (theta == null).  Segments are sorted by their first column
+// and tile [col_lo, col_hi) without overlap.
+struct Segment {
   float* theta;
   float* s0;
   float* s1;
-  long long grad_offset;
-  long long numel;
 };
 
 // Head of the workspace.
@@ -71,11 +71,15 @@ struct StepParams {
   float* gbar;               // mean gradient, laid out like one gradient row
   double* partials;          // one sum of squares per workgroup
   const WsHeader* header;    // clip_scale is read from here by k_apply
-  // tensors
-  DevTensor single;          // used when there is exactly one tensor
-  const DevTensor* table;    // [T]
-  const int* chunk_begin;    // [T+1] first chunk of each tensor, then the total
-  int T;
+  // segments (tensors and gaps) in gradient-row column order
+  Segment single;            // the one tensor when there is exactly one
+  const Segment* table;      // [S]
+  const unsigned* starts;    // [S+1] first column of each segment, then col_hi
+  int S;
+  long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
+  long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
+  int chunk_base;            // chunk id of workgroup 0 of this launch
+  int chunk_end;             // one past the last chunk this launch covers
 };
 
 // ---------------------------------------------------------------------------
@@ -151,21 +155,22 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
 constexpr int kUploadBatch = 64;
 
 struct UploadArgs {
-  int first, count, total_chunks, is_last;
-  DevTensor t[kUploadBatch];
-  int chunk_begin[kUploadBatch];
+  int first, count, is_last;
+  unsigned end_col;
+  Segment seg[kUploadBatch];
+  unsigned start[kUploadBatch];
 };
 
-// Descriptors travel in the kernel-argument buffer, so the host array is
-// consumed at launch time and no host-to-device copy has to be ordered.
-__global__ __launch_bounds__(kUploadBatch) void k_upload_table(UploadArgs a, DevTensor* __restrict__ table,
-                                                                 int* __restrict__ chunk_begin, int T) {
+// Segment descriptors travel in the kernel-argument buffer, so the host array
+// is consumed at launch time and no host-to-device copy has to be ordered.
+__global__ __launch_bounds__(kUploadBatch) void k_upload_table(UploadArgs a, Segment* __restrict__ table,
+                                                                 unsigned* __restrict__ starts, int S) {
   const int i = threadIdx.x;
   if (i < a.count) {
-    table[a.first + i] = a.t[i];
-    chunk_begin[a.first + i] = a.chunk_begin[i];
+    table[a.first + i] = a.seg[i];
+    starts[a.first + i] = a.start[i];
   }
-  if (i == 0 && a.is_last) chunk_begin[T] = a.total_chunks;
+  if (i == 0 && a.is_last) starts[S] = a.end_col;
 }
 
 // ---------------------------------------------------------------------------
@@ -199,12 +204,56 @@ __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__
     for (int v = 0; v < V; ++v) acc[v] += r[u][v];
 }
 
-template <int V, int U, bool NT>
+template <int V, int B, bool NT>
+__device__ __forceinline__ void load_rows(f4 (&r)[B][V], const float* __restrict__ grads, long long ld,
+                                          long long colbase, const int* __restrict__ sel_idx, int j,
+                                          const unsigned (&toff)[V]) {
+#pragma unroll
+  for (int u = 0; u < B; ++u) {
+    const long long k = sel_idx[j + u];
+    const char* rowbase = reinterpret_cast<const char*>(grads + k * ld + colbase);
+#pragma unroll
+    for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+  }
+}
+
+template <int V, int B>
+__device__ __forceinline__ void accumulate(f4 (&acc)[V], const f4 (&r)[B][V]) {
+#pragma unroll
+  for (int u = 0; u < B; ++u)
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] += r[u][v];
+}
+
+// FLAGS bit 1: the workgroup's wavefronts meet at a barrier after every batch,
+// so a workgroup reads its whole chunk of one row as one burst.
+// FLAGS bit 2: software pipelining: the next batch is requested before the
+// current one is added, so a wavefront always has a batch in flight.
+// Either way rows are added in ascending order.
+template <int V, int U, bool NT, int FLAGS>
 __device__ __forceinline__ void sum_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
                                          long long colbase, const int* __restrict__ sel_idx, int N,
                                          const unsigned (&toff)[V]) {
   int j = 0;
-  for (; j + U <= N; j += U) add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, j, toff);
+  if constexpr ((FLAGS & 4) != 0) {
+    const int nb = N / U;
+    f4 r0[U][V], r1[U][V];
+    if (nb > 0) load_rows<V, U, NT>(r0, grads, ld, colbase, sel_idx, 0, toff);
+    for (int b = 0; b < nb; b += 2) {
+      if (b + 1 < nb) load_rows<V, U, NT>(r1, grads, ld, colbase, sel_idx, (b + 1) * U, toff);
+      accumulate<V, U>(acc, r0);
+      if (b + 1 < nb) {
+        if (b + 2 < nb) load_rows<V, U, NT>(r0, grads, ld, colbase, sel_idx, (b + 2) * U, toff);
+        accumulate<V, U>(acc, r1);
+      }
+    }
+    j = nb * U;
+  } else {
+    for (; j + U <= N; j += U) {
+      add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, j, toff);
+      if constexpr ((FLAGS & 2) != 0) __syncthreads();
+    }
+  }
   if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 8; } }
   if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 4; } }
   if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 2; } }
@@ -265,160 +314,205 @@ __device__ __forceinline__ double block_sum(float x, float* lds) {
   return s;
 }
 
-// Which tensor a chunk belongs to: the last j with chunk_begin[j] <= c.
-__device__ __forceinline__ int find_tensor(const int* cb, int T, int c) {
-  int lo = 0, hi = T;                                 // invariant: cb[lo] <= c < cb[hi]
+// Which segment holds column x: the last j with starts[j] <= x.  Requires
+// starts[0] <= x < starts[S].
+__device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsigned x) {
+  int lo = 0, hi = S;                                 // invariant: starts[lo] <= x < starts[hi]
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (cb[mid] <= c) lo = mid; else hi = mid;
+    if (starts[mid] <= x) lo = mid; else hi = mid;
   }
   return lo;
 }
 
 // SRC_ROWS: the gradient comes from summing the kept rows (MODE 0..2 updates
-// directly; MODE kClipReduce stores the mean and a per-block sum of squares).
+// directly; MODE kClipReduce stores the mean and a per-chunk sum of squares).
 // !SRC_ROWS: the gradient is the stored mean times the clip scale (MODE 0..2).
 //
-// Work is cut into chunks of BS*V float4 groups.  Groups are aligned to the
-// gradient row (not to theta): group g of a tensor covers elements
-// [4g-h, 4g-h+4) with h = grad_offset mod 4, so row loads are 16-byte aligned
-// whenever grads and ld are; theta/state accesses may then be only 4-byte
-// aligned.  Chunks fully inside a tensor take the vector path with no
-// per-lane tests; the first and last chunk of a tensor take the edge path.
+// Work is cut in the column space of a gradient row, not per tensor: chunk c
+// covers the BS*V float4 groups starting at column base + c*4*BS*V.  Every
+// chunk is full width whatever the tensor sizes are, row loads are always
+// aligned 16-byte groups, and small tensors share chunks.  theta/state are
+// found through the sorted segment table: a chunk lying inside one tensor
+// (nearly all of them) takes the uniform path with wave-uniform pointers and
+// float4 accesses (4-byte aligned only, since a tensor may start anywhere in
+// the row); a chunk holding a tensor boundary looks segments up per lane.
 template <int MODE, class S, bool MULTI, bool SRC_ROWS>
 __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
   constexpr int BS = S::BS, V = S::V, U = S::U;
   constexpr bool NT = S::NT;
-  extern __shared__ int cb_lds[];                      // MULTI: chunk_begin[T+1]
+  constexpr long long CH = 4LL * BS * V;               // columns per chunk
+  extern __shared__ unsigned starts_lds[];             // MULTI: starts[S+1]
   __shared__ float red_lds[BS / 64];
 
   if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
 
-  DevTensor tz;
-  int c = blockIdx.x;
   if constexpr (MULTI) {
-    for (int i = threadIdx.x; i <= p.T; i += BS) cb_lds[i] = p.chunk_begin[i];
+    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
     __syncthreads();
-    const int j = __builtin_amdgcn_readfirstlane(find_tensor(cb_lds, p.T, c));   // same in every lane
-    c -= __builtin_amdgcn_readfirstlane(cb_lds[j]);
-    tz = p.table[j];
-  } else {
-    tz = p.single;
   }
+  const long long span_end4 = (p.col_hi + 3) & ~3LL;   // rows are readable up to here (<= ld)
 
-  const int h = (int)(tz.grad_offset & 3);
-  const long long group0 = (long long)c * (BS * V);
-  const long long e_first = 4 * group0 - h;            // first element this chunk covers (may be < 0)
-  const long long colbase = tz.grad_offset + e_first;  // same thing inside a gradient row
-  const bool interior = (e_first >= 0) && (e_first + 4LL * BS * V <= tz.numel);
+  for (int chunk_id = (int)blockIdx.x + p.chunk_base; chunk_id < p.chunk_end; chunk_id += (int)gridDim.x) {
+    const long long c0 = p.base + (long long)chunk_id * CH;   // first column of the chunk, multiple of 4
 
-  float scale = 1.0f;
-  if constexpr (!SRC_ROWS) scale = p.header->clip_scale;
+    // the segment holding the chunk's first column (clamped into the covered range)
+    Segment seg;
+    long long seg_start, seg_end;
+    int j0 = 0;
+    if constexpr (MULTI) {
+      const long long x = c0 < p.col_lo ? p.col_lo : c0;
+      j0 = __builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)x));
+      seg_start = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[j0]);
+      seg_end = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[j0 + 1]);
+      seg = p.table[j0];
+    } else {
+      seg_start = p.col_lo;
+      seg_end = p.col_hi;
+      seg = p.single;
+    }
+    const bool uniform = (c0 >= seg_start) && (c0 + CH <= seg_end) && (seg.theta != nullptr);
 
-  float sumsq = 0.0f;
+    float scale = 1.0f;
+    if constexpr (!SRC_ROWS) scale = p.header->clip_scale;
+    float sumsq = 0.0f;
 
-  if (interior) {
+    // Lanes whose group starts past the readable end of the row (only in the
+    // last chunk) re-read the chunk's first group and take no further part.
     unsigned toff[V];
+    bool valid[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) toff[v] = (unsigned)S::group_of(v) * 16u;
-
-    // issue the parameter/state loads first so they overlap the row loop
-    f4 th[V], a[V], b[V];
-    if constexpr (MODE != kClipReduce) {
-#pragma unroll
-      for (int v = 0; v < V; ++v) {
-        th[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(tz.theta + e_first) + toff[v]);
-        if constexpr (MODE >= kMomentum) a[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(tz.s0 + e_first) + toff[v]);
-        if constexpr (MODE == kRmspropMom) b[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(tz.s1 + e_first) + toff[v]);
-      }
+    for (int v = 0; v < V; ++v) {
+      const int g = S::group_of(v);
+      valid[v] = uniform || (c0 + 4LL * g < span_end4);
+      toff[v] = valid[v] ? (unsigned)g * 16u : 0u;
     }
 
     f4 g[V];
     if constexpr (SRC_ROWS) {
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] = f4{0.f, 0.f, 0.f, 0.f};
-      sum_rows<V, U, NT>(g, p.grads, p.ld, colbase, p.sel_idx, p.N, toff);
+      sum_rows<V, U, NT, S::MAP>(g, p.grads, p.ld, c0, p.sel_idx, p.N, toff);
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] *= p.inv_n;
     } else {
 #pragma unroll
       for (int v = 0; v < V; ++v)
-        g[v] = *reinterpret_cast<const f4*>(reinterpret_cast<const char*>(p.gbar + colbase) + toff[v]) * scale;
+        g[v] = *reinterpret_cast<const f4*>(reinterpret_cast<const char*>(p.gbar + c0) + toff[v]) * scale;
+    }
+
+    if (uniform) {
+      // ---- the whole chunk lies inside one tensor ------------------------------------
+      const long long e_first = c0 - seg_start;        // element of the tensor at the chunk's first column
+      if constexpr (MODE == kClipReduce) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          *reinterpret_cast<f4*>(reinterpret_cast<char*>(p.gbar + c0) + toff[v]) = g[v];
+          sumsq = fmaf(g[v].x, g[v].x, sumsq);
+          sumsq = fmaf(g[v].y, g[v].y, sumsq);
+          sumsq = fmaf(g[v].z, g[v].z, sumsq);
+          sumsq = fmaf(g[v].w, g[v].w, sumsq);
+        }
+      } else {
+        // fetch theta/state for all groups first (independent loads in flight together)
+        f4 th[V], a[V], b[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          th[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.theta + e_first) + toff[v]);
+          if constexpr (MODE >= kMomentum) a[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.s0 + e_first) + toff[v]);
+          if constexpr (MODE == kRmspropMom) b[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.s1 + e_first) + toff[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          update_vec<MODE>(g[v], th[v], a[v], b[v], p);
+          *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.theta + e_first) + toff[v]) = th[v];
+          if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.s0 + e_first) + toff[v]) = a[v];
+          if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.s1 + e_first) + toff[v]) = b[v];
+        }
+      }
+    } else {
+      // ---- the chunk holds a tensor boundary, a gap, or the end of the row ---------------
+      // One group after the other (this path is rare; it favours few registers
+      // over loads in flight).
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const long long gcol = c0 + 4LL * S::group_of(v);
+        if (gcol >= span_end4) continue;
+        const f4 gv = g[v];
+        if constexpr (MODE == kClipReduce) {
+          // the stored mean is laid out like a row: whole groups, gaps included
+          *reinterpret_cast<f4*>(p.gbar + gcol) = gv;
+        }
+        if (gcol + 4 <= p.col_lo || gcol >= p.col_hi) continue;
+        // segment of the group's first covered column
+        int j = 0;
+        long long s_start = p.col_lo, s_end = p.col_hi;
+        Segment sg = seg;
+        if constexpr (MULTI) {
+          const long long x = gcol < p.col_lo ? p.col_lo : gcol;
+          j = find_segment(starts_lds, p.S, (unsigned)x);
+          s_start = starts_lds[j];
+          s_end = starts_lds[j + 1];
+          sg = p.table[j];
+        }
+        if (gcol >= s_start && gcol + 4 <= s_end) {
+          // whole group inside one segment
+          if (sg.theta == nullptr) continue;           // a gap
+          if constexpr (MODE == kClipReduce) {
+            sumsq = fmaf(gv.x, gv.x, sumsq);
+            sumsq = fmaf(gv.y, gv.y, sumsq);
+            sumsq = fmaf(gv.z, gv.z, sumsq);
+            sumsq = fmaf(gv.w, gv.w, sumsq);
+          } else {
+            const long long e = gcol - s_start;
+            f4 th, a, b;
+            th = *reinterpret_cast<const f4u*>(sg.theta + e);
+            if constexpr (MODE >= kMomentum) a = *reinterpret_cast<const f4u*>(sg.s0 + e);
+            if constexpr (MODE == kRmspropMom) b = *reinterpret_cast<const f4u*>(sg.s1 + e);
+            update_vec<MODE>(gv, th, a, b, p);
+            *reinterpret_cast<f4u*>(sg.theta + e) = th;
+            if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(sg.s0 + e) = a;
+            if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(sg.s1 + e) = b;
+          }
+        } else {
+          // the group is cut by a boundary: element by element
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const long long col = gcol + q;
+            if (col < p.col_lo || col >= p.col_hi) continue;
+            if constexpr (MULTI) {
+              while (col >= s_end) {                   // segments are non-empty: at most 3 steps per group
+                ++j;
+                s_start = s_end;
+                s_end = starts_lds[j + 1];
+                sg = p.table[j];
+              }
+            }
+            if (sg.theta == nullptr) continue;         // a gap
+            const float gq = gv[q];
+            if constexpr (MODE == kClipReduce) {
+              sumsq = fmaf(gq, gq, sumsq);
+            } else {
+              const long long e = col - s_start;
+              float t1 = sg.theta[e], a1 = 0.f, b1 = 0.f;
+              if constexpr (MODE >= kMomentum) a1 = sg.s0[e];
+              if constexpr (MODE == kRmspropMom) b1 = sg.s1[e];
+              update_elem<MODE>(gq, t1, a1, b1, p);
+              sg.theta[e] = t1;
+              if constexpr (MODE >= kMomentum) sg.s0[e] = a1;
+              if constexpr (MODE == kRmspropMom) sg.s1[e] = b1;
+            }
+          }
+        }
+      }
     }
 
     if constexpr (MODE == kClipReduce) {
-#pragma unroll
-      for (int v = 0; v < V; ++v) {
-        *reinterpret_cast<f4*>(reinterpret_cast<char*>(p.gbar + colbase) + toff[v]) = g[v];
-        sumsq = fmaf(g[v].x, g[v].x, sumsq);
-        sumsq = fmaf(g[v].y, g[v].y, sumsq);
-        sumsq = fmaf(g[v].z, g[v].z, sumsq);
-        sumsq = fmaf(g[v].w, g[v].w, sumsq);
-      }
-    } else {
-#pragma unroll
-      for (int v = 0; v < V; ++v) {
-        update_vec<MODE>(g[v], th[v], a[v], b[v], p);
-        *reinterpret_cast<f4u*>(reinterpret_cast<char*>(tz.theta + e_first) + toff[v]) = th[v];
-        if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(tz.s0 + e_first) + toff[v]) = a[v];
-        if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(tz.s1 + e_first) + toff[v]) = b[v];
-      }
+      const double s = block_sum<BS>(sumsq, red_lds);
+      if (threadIdx.x == 0) p.partials[chunk_id] = s;
+      __syncthreads();                                 // red_lds is reused by the next chunk
     }
-  } else {
-    // Edge chunk: per float4 group, a full group still uses one 16-byte load
-    // per row; a group cut by the tensor's start or end goes element by element.
-    for (int v = 0; v < V; ++v) {
-      const long long e0 = e_first + 4LL * S::group_of(v);
-      if (e0 + 4 <= 0 || e0 >= tz.numel) continue;
-      const bool full = (e0 >= 0) && (e0 + 4 <= tz.numel);
-      float gv[4] = {0.f, 0.f, 0.f, 0.f};
-      bool ok[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) ok[q] = (e0 + q >= 0) && (e0 + q < tz.numel);
-      const long long col = tz.grad_offset + e0;
-      if constexpr (SRC_ROWS) {
-        if (full) {
-          f4 acc[1] = {f4{0.f, 0.f, 0.f, 0.f}};
-          const unsigned z[1] = {0u};
-          sum_rows<1, U, NT>(acc, p.grads, p.ld, col, p.sel_idx, p.N, z);
-          gv[0] = acc[0].x; gv[1] = acc[0].y; gv[2] = acc[0].z; gv[3] = acc[0].w;
-        } else {
-          for (int j = 0; j < p.N; ++j) {
-            const float* row = p.grads + (long long)p.sel_idx[j] * p.ld + col;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) if (ok[q]) gv[q] += row[q];
-          }
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) gv[q] *= p.inv_n;
-      } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) if (ok[q]) gv[q] = p.gbar[col + q] * scale;
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (!ok[q]) continue;
-        const long long e = e0 + q;
-        if constexpr (MODE == kClipReduce) {
-          p.gbar[col + q] = gv[q];
-          sumsq = fmaf(gv[q], gv[q], sumsq);
-        } else {
-          float th = tz.theta[e], a = 0.f, b = 0.f;
-          if constexpr (MODE >= kMomentum) a = tz.s0[e];
-          if constexpr (MODE == kRmspropMom) b = tz.s1[e];
-          update_elem<MODE>(gv[q], th, a, b, p);
-          tz.theta[e] = th;
-          if constexpr (MODE >= kMomentum) tz.s0[e] = a;
-          if constexpr (MODE == kRmspropMom) tz.s1[e] = b;
-        }
-      }
-    }
-  }
-
-  if constexpr (MODE == kClipReduce) {
-    const double s = block_sum<BS>(sumsq, red_lds);
-    if (threadIdx.x == 0) p.partials[blockIdx.x] = s;
-  }
+  }  // chunk loop
 }
 
 // One workgroup adds the per-block sums of squares in a fixed order (fp64),

@@ -59,7 +59,7 @@ def test_workspace_bytes():
     assert big >= small + 4 * (1 << 20)            # room for the stored mean gradient
     more_t = bs.bsgd_workspace_bytes(1 << 20, 4, 1, 300, hy)
     assert more_t > small
-    for bad in ((-1, 4, 1, 1), (10, 0, 1, 1), (10, 4, -1, 1), (10, 250, 7, 1), (10, 4, 1, 0), (10, 4, 1, 8193)):
+    for bad in ((-1, 4, 1, 1), (10, 0, 1, 1), (10, 4, -1, 1), (10, 250, 7, 1), (10, 4, 1, 0), (10, 4, 1, 4097)):
         with pytest.raises(bs.BsgdError):
             bs.bsgd_workspace_bytes(*bad, hy)
 
@@ -113,6 +113,10 @@ def test_host_side_argument_checks_enqueue_nothing():
     assert ru(tensors=neg) == bs.BSGD_ERR_ARG
     odd = bs.make_tensors([(A + 2, A, A, 0, 100)])
     assert ru(tensors=odd) == bs.BSGD_ERR_ARG         # theta not 4-byte aligned
+    # two tensors may not claim the same gradient columns (whatever order they are listed in)
+    big_ws = 1 << 22
+    clash = bs.make_tensors([(A, A, A, 50, 100), (A, A, A, 0, 51)])
+    assert ru(tensors=clash, T=2, ld=152, nbytes=big_ws) == bs.BSGD_ERR_ARG
     # clipping needs the larger workspace
     hyc = bs.make_hyper("sgd", 0.1, clip_norm=1.0)
     need = bs.bsgd_workspace_bytes(100, 4, 1, 1, hyc)

@@ -116,6 +116,30 @@ def test_misaligned_tensor_starts(opt, shift, goff):
     c.compare()
 
 
+def test_tensors_listed_out_of_order_with_gaps():
+    # descriptors in arbitrary order, holes between tensors, first tensor not at column 0
+    layout = [(9000, 2500), (7, 1000), (4001, 3), (1500, 2501), (4100, 4099), (8300, 64)]
+    c = Case(5, 2, layout, "rmsprop_mom", seed=21)
+    for _ in range(2):
+        g, t = c.draw()
+        # poison the gap columns: they belong to no tensor and must not matter
+        covered = np.zeros(c.ld, bool)
+        for o, n in layout:
+            covered[o:o + n] = True
+        g[:, ~covered] = np.nan
+        c.both(g, t)
+    c.compare()
+    cc = Case(5, 2, layout, "momentum", seed=22, hyper=dict(clip_norm=0.01))
+    for _ in range(2):
+        g, t = cc.draw()
+        covered = np.zeros(cc.ld, bool)
+        for o, n in layout:
+            covered[o:o + n] = True
+        g[:, ~covered] = 1e3            # finite garbage in the gaps must not enter the norm
+        cc.both(g, t)
+    cc.compare()
+
+
 def test_many_tensors_multiple_upload_batches_and_empty_ones():
     r = np.random.default_rng(5)
     sizes = [int(x) for x in r.integers(0, 700, 333)]          # some are empty
