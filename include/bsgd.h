@@ -151,23 +151,26 @@ int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t*
 int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float* scale_out);
 
 /* Launch shape of the reduce/update kernel, process-wide; for benchmarking.
- * A shape is (block, vec, unroll, nontemporal, map):
+ * A shape is (block, vec, unroll, nontemporal):
  *   block        threads per workgroup
  *   vec          float4 columns per thread
  *   unroll       kept rows loaded per batch before the first add
  *   nontemporal  0/1: gradient rows are loaded with the streaming hint
- *   map          0: workgroup-strided columns, 1: each wavefront reads one
- *                contiguous piece of a row
  * Every shape adds the kept rows in the same order, so results do not depend
  * on it.  By default the library picks a shape from the problem size (the
  * widest chunk that still fills every compute unit several times over).
  * bsgd_set_tuning pins a compiled-in shape (-1 keeps a field of the current
- * one; all five -1 returns to the automatic choice) and returns BSGD_ERR_ARG
+ * one; all four -1 returns to the automatic choice) and returns BSGD_ERR_ARG
  * when that combination is not compiled in; bsgd_num_shapes / bsgd_get_shape
- * enumerate them (out5 is HOST int32[5] in the order above). */
-int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal, int32_t map);
+ * enumerate them (out4 is HOST int32[4] in the order above). */
+int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal);
 int bsgd_num_shapes(void);
-int bsgd_get_shape(int32_t i, int32_t* out5);
+int bsgd_get_shape(int32_t i, int32_t* out4);
+
+/* How many launches of the reduce/update kernel the calling thread's last
+ * bsgd_step / bsgd_reduce_update enqueued (a step is cut into launches that
+ * each fill the chip once; a clipped step counts both of its passes). */
+int bsgd_last_launch_count(void);
 
 /* Measurement aid, not part of the step: a plain device-to-device copy of
  * `bytes` bytes (a multiple of 16; both pointers DEVICE, 16-byte aligned,

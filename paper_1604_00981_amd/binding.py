@@ -74,8 +74,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_last_selection.restype = ctypes.c_int
     lib.bsgd_last_clip.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float)]
     lib.bsgd_last_clip.restype = ctypes.c_int
-    lib.bsgd_set_tuning.argtypes = [i32, i32, i32, i32, i32]
+    lib.bsgd_set_tuning.argtypes = [i32, i32, i32, i32]
     lib.bsgd_set_tuning.restype = ctypes.c_int
+    lib.bsgd_last_launch_count.argtypes = []
+    lib.bsgd_last_launch_count.restype = ctypes.c_int
     lib.bsgd_num_shapes.argtypes = []
     lib.bsgd_num_shapes.restype = ctypes.c_int
     lib.bsgd_get_shape.argtypes = [i32, ctypes.POINTER(i32)]
@@ -210,16 +212,20 @@ def bsgd_last_clip(workspace: DevPtr, stream=None) -> Tuple[float, float]:
     return nrm.value, sc.value
 
 
-def bsgd_set_tuning(block: int = -1, vec: int = -1, unroll: int = -1, nontemporal: int = -1, map: int = -1) -> None:
-    _check(load_library().bsgd_set_tuning(block, vec, unroll, nontemporal, map), "bsgd_set_tuning")
+def bsgd_set_tuning(block: int = -1, vec: int = -1, unroll: int = -1, nontemporal: int = -1) -> None:
+    _check(load_library().bsgd_set_tuning(block, vec, unroll, nontemporal), "bsgd_set_tuning")
+
+
+def bsgd_last_launch_count() -> int:
+    return load_library().bsgd_last_launch_count()
 
 
 def bsgd_num_shapes() -> int:
     return load_library().bsgd_num_shapes()
 
 
-def bsgd_get_shape(i: int) -> Tuple[int, int, int, int, int]:
-    out = (ctypes.c_int32 * 5)()
+def bsgd_get_shape(i: int) -> Tuple[int, int, int, int]:
+    out = (ctypes.c_int32 * 4)()
     _check(load_library().bsgd_get_shape(i, out), "bsgd_get_shape")
     return tuple(out)
 

@@ -40,28 +40,28 @@ bool clip_on(const bsgd_hyper* h) { return h && h->clip_norm > 0.0f && std::isfi
 using StepKernel = void (*)(StepParams);
 
 struct Variant {
-  int BS, V, U, NT, MAP;
+  int BS, V, U, NT;
   StepKernel rows[4][2];     // [mode incl. clip-reduce][multi]   gradient from the kept rows
   StepKernel apply[3][2];    // [mode][multi]                      gradient from the stored mean
 };
 
-#define BSGD_SHAPE(BS, V, U, NT, MAP) Shape<BS, V, U, (NT) != 0, MAP>
-#define BSGD_VARIANT(BS, V, U, NT, MAP)                                                                      \
-  {BS, V, U, NT, MAP,                                                                                        \
-   {{k_step<kSgd, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kSgd, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>},               \
-    {k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>},     \
-    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>}, \
-    {k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT, MAP), false, true>, k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT, MAP), true, true>}}, \
-   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>},               \
-    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>},     \
-    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0, MAP), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0, MAP), true, false>}}}
+#define BSGD_SHAPE(BS, V, U, NT) Shape<BS, V, U, (NT) != 0>
+#define BSGD_VARIANT(BS, V, U, NT)                                                                           \
+  {BS, V, U, NT,                                                                                        \
+   {{k_step<kSgd, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kSgd, BSGD_SHAPE(BS, V, U, NT), true, true>},               \
+    {k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), true, true>},     \
+    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), true, true>}, \
+    {k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), true, true>}}, \
+   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0), true, false>},               \
+    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0), true, false>},     \
+    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0), true, false>}}}
 
 // Ordered widest chunk first (the automatic choice walks it in order).  A
 // build may supply its own list.
 #ifndef BSGD_VARIANT_LIST
 #define BSGD_VARIANT_LIST                                                                      \
-  BSGD_VARIANT(256, 8, 2, 1, 0), BSGD_VARIANT(256, 4, 2, 1, 0), BSGD_VARIANT(256, 2, 4, 1, 0), \
-  BSGD_VARIANT(256, 1, 8, 1, 0), BSGD_VARIANT(256, 8, 2, 0, 0)
+  BSGD_VARIANT(256, 8, 2, 1), BSGD_VARIANT(256, 4, 2, 1), BSGD_VARIANT(256, 2, 4, 1), \
+  BSGD_VARIANT(256, 1, 8, 1), BSGD_VARIANT(256, 8, 2, 0)
 #endif
 
 const Variant kVariants[] = {BSGD_VARIANT_LIST};
@@ -96,6 +96,7 @@ WsLayout layout(long long span, int T, bool clip) {
 }
 
 std::atomic<int> g_variant{-1};                      // -1: choose by problem size
+thread_local int t_last_launches = 0;                // reduce/update launches of this thread's last call
 
 // Automatic choice: the table is ordered widest chunk first; take the first
 // shape that still yields enough workgroups to fill every CU several times.
@@ -133,7 +134,6 @@ long long round_size(StepKernel fn, int block, size_t lds) {
   struct Entry { StepKernel fn; size_t lds; long long n; };
   static std::mutex mu;
   static std::vector<Entry> cache;
-  static const int forced_per_cu = [] { const char* e = getenv("BSGD_BLOCKS_PER_CU"); return e ? atoi(e) : 0; }();
   std::lock_guard<std::mutex> lock(mu);
   for (const Entry& e : cache)
     if (e.fn == fn && e.lds == lds) return e.n;
@@ -142,7 +142,6 @@ long long round_size(StepKernel fn, int block, size_t lds) {
     per_cu = 1;
   const int cap = (8 * 64) / block > 0 ? (8 * 64) / block : 1;
   if (per_cu > cap) per_cu = cap;
-  if (forced_per_cu > 0) per_cu = forced_per_cu;
   const long long n = (long long)per_cu * compute_units();
   cache.push_back(Entry{fn, lds, n});
   return n;
@@ -150,21 +149,20 @@ long long round_size(StepKernel fn, int block, size_t lds) {
 
 // Enqueue the work on `chunks` chunks as a sequence of near-equal launches of
 // at most one round of workgroups each, one chunk per workgroup.
-// BSGD_LAUNCH_MODE (read once) selects the alternatives kept for comparison:
-// "single" = everything in one launch, "persistent" = one launch of one round
-// of workgroups that stride through the chunk list.
+// BSGD_LAUNCH_MODE (environment, read once) selects the alternatives kept for
+// comparison: "single" = everything in one launch, "persistent" = one launch
+// of one round of workgroups that stride through the chunk list.
 int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p) {
   if (chunks <= 0) return BSGD_OK;
   if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
-  static const size_t lds_pad = [] { const char* e = getenv("BSGD_LDS_PAD"); return e ? (size_t)atol(e) : (size_t)0; }();
   static const int mode = [] {
     const char* e = getenv("BSGD_LAUNCH_MODE");
     if (e == nullptr) return 1;
     return strcmp(e, "persistent") == 0 ? 0 : strcmp(e, "single") == 0 ? 2 : 1;
   }();
-  lds += lds_pad;                                    // experiment knob: throttles workgroups per CU
   const long long round = round_size(fn, block, lds);
   auto go = [&](long long base, long long end, long long grid) -> int {
+    ++t_last_launches;
     p.chunk_base = (int)base;
     p.chunk_end = (int)end;
     void* args[] = {&p};
@@ -172,19 +170,15 @@ int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t s
     return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
   };
   if (mode == 2) return go(0, chunks, chunks);
-  if (mode == 1) {
-    static const int cpb = [] { const char* e = getenv("BSGD_CHUNKS_PER_BLOCK"); return e && atoi(e) > 0 ? atoi(e) : 1; }();
-    const long long cap = round * cpb;               // chunks per launch
-    const long long launches = (chunks + cap - 1) / cap;
-    const long long per = (chunks + launches - 1) / launches;
-    for (long long base = 0; base < chunks; base += per) {
-      const long long n = chunks - base < per ? chunks - base : per;
-      int rc = go(base, base + n, n < round ? n : round);
-      if (rc != BSGD_OK) return rc;
-    }
-    return BSGD_OK;
+  if (mode == 0) return go(0, chunks, chunks < round ? chunks : round);
+  const long long launches = (chunks + round - 1) / round;
+  const long long per = (chunks + launches - 1) / launches;
+  for (long long base = 0; base < chunks; base += per) {
+    const long long n = chunks - base < per ? chunks - base : per;
+    int rc = go(base, base + n, n);
+    if (rc != BSGD_OK) return rc;
   }
-  return go(0, chunks, chunks < round ? chunks : round);
+  return BSGD_OK;
 }
 
 bool check_select_args(const float* arrival_t, int N, int b) {
@@ -291,6 +285,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
 
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
                           int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream) {
+  t_last_launches = 0;
   if (plan.S == 0) return BSGD_OK;
   const int mode = hyper->opt;
   const bool clip = clip_on(hyper);
@@ -411,18 +406,18 @@ int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float*
   return BSGD_OK;
 }
 
-int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal, int32_t map) {
-  if (block < 0 && vec < 0 && unroll < 0 && nontemporal < 0 && map < 0) {
+int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal) {
+  if (block < 0 && vec < 0 && unroll < 0 && nontemporal < 0) {
     g_variant.store(-1, std::memory_order_relaxed);    // back to the automatic choice
     return BSGD_OK;
   }
   const int cur_i = g_variant.load(std::memory_order_relaxed);
   const Variant& cur = kVariants[cur_i < 0 ? 0 : cur_i];
   const int BS = block < 0 ? cur.BS : block, V = vec < 0 ? cur.V : vec, U = unroll < 0 ? cur.U : unroll;
-  const int NT = nontemporal < 0 ? cur.NT : nontemporal, MAP = map < 0 ? cur.MAP : map;
+  const int NT = nontemporal < 0 ? cur.NT : nontemporal;
   for (int i = 0; i < kNumVariants; ++i) {
     const Variant& v = kVariants[i];
-    if (v.BS == BS && v.V == V && v.U == U && v.NT == NT && v.MAP == MAP) {
+    if (v.BS == BS && v.V == V && v.U == U && v.NT == NT) {
       g_variant.store(i, std::memory_order_relaxed);
       return BSGD_OK;
     }
@@ -430,12 +425,14 @@ int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontempo
   return BSGD_ERR_ARG;
 }
 
+int bsgd_last_launch_count(void) { return t_last_launches; }
+
 int bsgd_num_shapes(void) { return kNumVariants; }
 
-int bsgd_get_shape(int32_t i, int32_t* out5) {
-  if (i < 0 || i >= kNumVariants || out5 == nullptr) return BSGD_ERR_ARG;
+int bsgd_get_shape(int32_t i, int32_t* out4) {
+  if (i < 0 || i >= kNumVariants || out4 == nullptr) return BSGD_ERR_ARG;
   const Variant& v = kVariants[i];
-  out5[0] = v.BS; out5[1] = v.V; out5[2] = v.U; out5[3] = v.NT; out5[4] = v.MAP;
+  out4[0] = v.BS; out4[1] = v.V; out4[2] = v.U; out4[3] = v.NT;
   return BSGD_OK;
 }
 

@@ -22,21 +22,18 @@ typedef f4 f4u __attribute__((aligned(4)));          // float4 that is only 4-by
 
 // Launch shape of the reduce/update kernel.
 //   BS   threads per workgroup
-//   V    float4 columns per thread (a chunk is BS*V float4 groups wide)
+//   V    float4 columns per thread (a chunk is BS*V float4 groups wide);
+//        thread t takes groups t, t+BS, ..., so each load instruction of a
+//        wavefront covers 1 KiB of contiguous row
 //   U    kept rows loaded per batch before the first add
 //   NT   gradient rows are loaded with the non-temporal (streaming) hint
-//   MAP  0: thread t takes groups t, t+BS, ...   (workgroup-strided)
-//        1: wave w takes V*64 consecutive groups (each wavefront reads one
-//           contiguous V KiB piece of a row)
-template <int BS_, int V_, int U_, bool NT_, int MAP_>
+template <int BS_, int V_, int U_, bool NT_>
 struct Shape {
-  static constexpr int BS = BS_, V = V_, U = U_, MAP = MAP_;
+  static constexpr int BS = BS_, V = V_, U = U_;
   static constexpr bool NT = NT_;
-  __device__ static __forceinline__ int group_of(int v) {
-    if constexpr ((MAP_ & 1) == 0) return v * BS_ + (int)threadIdx.x;
-    else return (((int)threadIdx.x >> 6) * V_ + v) * 64 + ((int)threadIdx.x & 63);
-  }
+  __device__ static __forceinline__ int group_of(int v) { return v * BS_ + (int)threadIdx.x; }
 };
+
 constexpr int kMaxWorkers = 256;
 
 enum Mode : int { kSgd = 0, kMomentum = 1, kRmspropMom = 2, kClipReduce = 3 };
@@ -204,64 +201,19 @@ __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__
     for (int v = 0; v < V; ++v) acc[v] += r[u][v];
 }
 
-template <int V, int B, bool NT>
-__device__ __forceinline__ void load_rows(f4 (&r)[B][V], const float* __restrict__ grads, long long ld,
-                                          long long colbase, const int* __restrict__ sel_idx, int j,
-                                          const unsigned (&toff)[V]) {
-#pragma unroll
-  for (int u = 0; u < B; ++u) {
-    const long long k = sel_idx[j + u];
-    const char* rowbase = reinterpret_cast<const char*>(grads + k * ld + colbase);
-#pragma unroll
-    for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
-  }
-}
-
-template <int V, int B>
-__device__ __forceinline__ void accumulate(f4 (&acc)[V], const f4 (&r)[B][V]) {
-#pragma unroll
-  for (int u = 0; u < B; ++u)
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] += r[u][v];
-}
-
-// FLAGS bit 1: the workgroup's wavefronts meet at a barrier after every batch,
-// so a workgroup reads its whole chunk of one row as one burst.
-// FLAGS bit 2: software pipelining: the next batch is requested before the
-// current one is added, so a wavefront always has a batch in flight.
-// Either way rows are added in ascending order.
-template <int V, int U, bool NT, int FLAGS>
+// All kept rows, in batches of U (then 8, 4, 2, 1 for what is left).
+template <int V, int U, bool NT>
 __device__ __forceinline__ void sum_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
                                          long long colbase, const int* __restrict__ sel_idx, int N,
                                          const unsigned (&toff)[V]) {
   int j = 0;
-  if constexpr ((FLAGS & 4) != 0) {
-    const int nb = N / U;
-    f4 r0[U][V], r1[U][V];
-    if (nb > 0) load_rows<V, U, NT>(r0, grads, ld, colbase, sel_idx, 0, toff);
-    for (int b = 0; b < nb; b += 2) {
-      if (b + 1 < nb) load_rows<V, U, NT>(r1, grads, ld, colbase, sel_idx, (b + 1) * U, toff);
-      accumulate<V, U>(acc, r0);
-      if (b + 1 < nb) {
-        if (b + 2 < nb) load_rows<V, U, NT>(r0, grads, ld, colbase, sel_idx, (b + 2) * U, toff);
-        accumulate<V, U>(acc, r1);
-      }
-    }
-    j = nb * U;
-  } else {
-    for (; j + U <= N; j += U) {
-      add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, j, toff);
-      if constexpr ((FLAGS & 2) != 0) __syncthreads();
-    }
-  }
+  for (; j + U <= N; j += U) add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, j, toff);
   if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 8; } }
   if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 4; } }
   if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 2; } }
   if constexpr (U > 1) { if ((N - j) & 1) { add_rows<V, 1, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 1; } }
 }
 
-// The optimizer update of one element; g is the (mean, possibly clipped)
-// aggregated gradient.
 // The library is compiled with floating-point contraction off and spells its
 // fused multiply-adds out, so an element gets the same bits whichever path
 // (vector or edge) and launch shape handles it.
@@ -392,7 +344,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
     if constexpr (SRC_ROWS) {
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] = f4{0.f, 0.f, 0.f, 0.f};
-      sum_rows<V, U, NT, S::MAP>(g, p.grads, p.ld, c0, p.sel_idx, p.N, toff);
+      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, p.N, toff);
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] *= p.inv_n;
     } else {

@@ -125,14 +125,14 @@ def test_host_side_argument_checks_enqueue_nothing():
 
 def test_tuning_rejects_unknown_shapes():
     with pytest.raises(bs.BsgdError):
-        bs.bsgd_set_tuning(192, 3, 7, 1, 0)
+        bs.bsgd_set_tuning(192, 3, 7, 1)
     bs.bsgd_set_tuning()                              # keep current
     n = bs.bsgd_num_shapes()
     assert n >= 1
     shapes = [bs.bsgd_get_shape(i) for i in range(n)]
     assert len(set(shapes)) == n
-    for blk, vec, unroll, nt, mp in shapes:
-        assert blk % 64 == 0 and vec >= 1 and unroll >= 1 and nt in (0, 1) and mp in (0, 1)
+    for blk, vec, unroll, nt in shapes:
+        assert blk % 64 == 0 and vec >= 1 and unroll >= 1 and nt in (0, 1)
     with pytest.raises(bs.BsgdError):
         bs.bsgd_get_shape(n)
 

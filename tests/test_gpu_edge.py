@@ -296,10 +296,12 @@ def test_every_compiled_launch_shape_gives_identical_bits():
             bs.bsgd_set_tuning(*shape)
             c = Case(23, 3, [(2, 20011), (20013, 5), (20018, 4100)], "rmsprop_mom", seed=17, hyper=dict(clip_norm=0.0))
             for _ in range(2):
-                c.gpu_step(*c.draw())
+                c.both(*c.draw())
+            c.compare()                                 # every shape against the oracle, not only against each other
             cc = Case(23, 3, [(2, 20011), (20013, 5), (20018, 4100)], "momentum", seed=18, hyper=dict(clip_norm=0.002))
             for _ in range(2):
-                cc.gpu_step(*cc.draw())
+                cc.both(*cc.draw())
+            cc.compare()
             results.append((c.gpu_arrays(), cc.gpu_arrays()))
     finally:
         bs.bsgd_set_tuning()                          # back to the automatic choice
