@@ -147,36 +147,28 @@ long long round_size(StepKernel fn, int block, size_t lds) {
   return n;
 }
 
-// Enqueue the work on `chunks` chunks as a sequence of near-equal launches of
-// at most one round of workgroups each, one chunk per workgroup.
-// BSGD_LAUNCH_MODE (environment, read once) selects the alternatives kept for
-// comparison: "single" = everything in one launch, "persistent" = one launch
-// of one round of workgroups that stride through the chunk list.
+// Enqueue the work on `chunks` chunks, one chunk per workgroup, as a sequence
+// of near-equal launches of at most one round of workgroups each.
+// BSGD_LAUNCH_MODE=single (environment, read once) puts everything in one
+// launch instead; kept for comparison.
 int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p) {
   if (chunks <= 0) return BSGD_OK;
   if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
-  static const int mode = [] {
+  static const bool single = [] {
     const char* e = getenv("BSGD_LAUNCH_MODE");
-    if (e == nullptr) return 1;
-    return strcmp(e, "persistent") == 0 ? 0 : strcmp(e, "single") == 0 ? 2 : 1;
+    return e != nullptr && strcmp(e, "single") == 0;
   }();
-  const long long round = round_size(fn, block, lds);
-  auto go = [&](long long base, long long end, long long grid) -> int {
-    ++t_last_launches;
-    p.chunk_base = (int)base;
-    p.chunk_end = (int)end;
-    void* args[] = {&p};
-    hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)grid), dim3(block), args, lds, stream);
-    return e == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
-  };
-  if (mode == 2) return go(0, chunks, chunks);
-  if (mode == 0) return go(0, chunks, chunks < round ? chunks : round);
+  long long round = single ? chunks : round_size(fn, block, lds);
+  if (2 * chunks < 5 * round) round = chunks;        // small problems are launch-bound: one launch
   const long long launches = (chunks + round - 1) / round;
   const long long per = (chunks + launches - 1) / launches;
   for (long long base = 0; base < chunks; base += per) {
     const long long n = chunks - base < per ? chunks - base : per;
-    int rc = go(base, base + n, n);
-    if (rc != BSGD_OK) return rc;
+    ++t_last_launches;
+    p.chunk_base = (int)base;
+    void* args[] = {&p};
+    hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)n), dim3(block), args, lds, stream);
+    if (e != hipSuccess) return BSGD_ERR_HIP;
   }
   return BSGD_OK;
 }

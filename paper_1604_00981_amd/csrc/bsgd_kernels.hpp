@@ -12,6 +12,10 @@
 //                    of squares, then scale the stored mean and update.
 #pragma once
 
+#ifndef BSGD_PIECE_WIDTH
+#define BSGD_PIECE_WIDTH(V) (V)
+#endif
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -76,7 +80,6 @@ struct StepParams {
   long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
   long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
   int chunk_base;            // chunk id of workgroup 0 of this launch
-  int chunk_end;             // one past the last chunk this launch covers
 };
 
 // ---------------------------------------------------------------------------
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
 // ---------------------------------------------------------------------------
 // Tensor table
 // ---------------------------------------------------------------------------
-constexpr int kUploadBatch = 64;
+constexpr int kUploadBatch = 128;                    // 128 x 28 bytes of descriptors fit the 4 KiB argument buffer
 
 struct UploadArgs {
   int first, count, is_last;
@@ -266,6 +269,56 @@ __device__ __forceinline__ double block_sum(float x, float* lds) {
   return s;
 }
 
+// theta/state update of the groups V0..V0+VN-1 of one chunk against ONE piece
+// (a tensor's column range, given relative to the chunk's first column):
+// lanes whose group lies whole inside the piece fetch theta/state together,
+// update, store; `done` collects which groups were handled.  Base addresses
+// are wave-uniform, lanes add their byte offset.  With kClipReduce the groups
+// only add to the sum of squares.
+template <int MODE, class S, int V0, int VN, int V>
+__device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&toff)[V], const bool (&valid)[V],
+                                             bool all, int lo_rel, int hi_rel, uintptr_t pth, uintptr_t ps0,
+                                             uintptr_t ps1, unsigned& done, float& sumsq, const StepParams& p) {
+  bool in[VN];
+#pragma unroll
+  for (int i = 0; i < VN; ++i) {
+    const int rel = 4 * S::group_of(V0 + i);
+    in[i] = all || (valid[V0 + i] && rel >= lo_rel && rel + 4 <= hi_rel);
+    done |= in[i] ? (1u << (V0 + i)) : 0u;
+  }
+  if constexpr (MODE == kClipReduce) {
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      if (in[i]) {
+        const f4 x = g[V0 + i];
+        sumsq = fmaf(x.x, x.x, sumsq);
+        sumsq = fmaf(x.y, x.y, sumsq);
+        sumsq = fmaf(x.z, x.z, sumsq);
+        sumsq = fmaf(x.w, x.w, sumsq);
+      }
+    }
+  } else {
+    f4 th[VN], a[VN], b[VN];
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      if (in[i]) {
+        th[i] = *reinterpret_cast<const f4u*>(pth + toff[V0 + i]);
+        if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(ps0 + toff[V0 + i]);
+        if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(ps1 + toff[V0 + i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      if (in[i]) {
+        update_vec<MODE>(g[V0 + i], th[i], a[i], b[i], p);
+        *reinterpret_cast<f4u*>(pth + toff[V0 + i]) = th[i];
+        if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(ps0 + toff[V0 + i]) = a[i];
+        if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(ps1 + toff[V0 + i]) = b[i];
+      }
+    }
+  }
+}
+
 // Which segment holds column x: the last j with starts[j] <= x.  Requires
 // starts[0] <= x < starts[S].
 __device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsigned x) {
@@ -305,7 +358,8 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
   }
   const long long span_end4 = (p.col_hi + 3) & ~3LL;   // rows are readable up to here (<= ld)
 
-  for (int chunk_id = (int)blockIdx.x + p.chunk_base; chunk_id < p.chunk_end; chunk_id += (int)gridDim.x) {
+  {
+    const int chunk_id = (int)blockIdx.x + p.chunk_base;   // one chunk per workgroup
     const long long c0 = p.base + (long long)chunk_id * CH;   // first column of the chunk, multiple of 4
 
     // the segment holding the chunk's first column (clamped into the covered range)
@@ -353,106 +407,162 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
         g[v] = *reinterpret_cast<const f4*>(reinterpret_cast<const char*>(p.gbar + c0) + toff[v]) * scale;
     }
 
+    // The segments ("pieces") the chunk's covered columns fall into: j0..j1.
+    int j1 = j0;
+    if constexpr (MULTI) {
+      if (!uniform) {
+        long long last = c0 + CH - 1;
+        if (last >= p.col_hi) last = p.col_hi - 1;
+        if (last < p.col_lo) last = p.col_lo;
+        j1 = __builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)last));
+      }
+    }
+
+    if constexpr (MODE == kClipReduce) {
+      // the stored mean is laid out like a row: whole groups, gaps included
+#pragma unroll
+      for (int v = 0; v < V; ++v)
+        if (valid[v]) *reinterpret_cast<f4*>(reinterpret_cast<char*>(p.gbar + c0) + toff[v]) = g[v];
+    }
+
+    unsigned done = 0;                                 // bit v: group v was handled as a whole by some piece
     if (uniform) {
-      // ---- the whole chunk lies inside one tensor ------------------------------------
-      const long long e_first = c0 - seg_start;        // element of the tensor at the chunk's first column
-      if constexpr (MODE == kClipReduce) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-          *reinterpret_cast<f4*>(reinterpret_cast<char*>(p.gbar + c0) + toff[v]) = g[v];
-          sumsq = fmaf(g[v].x, g[v].x, sumsq);
-          sumsq = fmaf(g[v].y, g[v].y, sumsq);
-          sumsq = fmaf(g[v].z, g[v].z, sumsq);
-          sumsq = fmaf(g[v].w, g[v].w, sumsq);
+      // ---- the chunk lies inside one tensor (almost always): every lane, all groups at once ---
+      const uintptr_t e_bytes = (uintptr_t)((c0 - seg_start) * 4);
+      piece_update<MODE, S, 0, V>(g, toff, valid, true, 0, 0, reinterpret_cast<uintptr_t>(seg.theta) + e_bytes,
+                                  reinterpret_cast<uintptr_t>(seg.s0) + e_bytes,
+                                  reinterpret_cast<uintptr_t>(seg.s1) + e_bytes, done, sumsq, p);
+    } else {
+      // ---- the chunk holds tensor boundaries, gaps or the end of the row -------------------
+      // Every group lies in at most one piece, so the pieces' loads can share
+      // one set of registers (different lanes): first all pieces fetch
+      // theta/state for the lanes they own, then everything is updated once,
+      // then all pieces store.  Groups go in two halves to bound registers.
+      auto piece = [&](int pj, Segment& sg, int& lo_rel, int& hi_rel, uintptr_t& e_bytes) {
+        sg = seg;
+        long long lo = seg_start, hi = seg_end;
+        if constexpr (MULTI) {
+          if (pj != j0) {
+            sg = p.table[pj];
+            lo = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj]);
+            hi = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj + 1]);
+          }
         }
-      } else {
-        // fetch theta/state for all groups first (independent loads in flight together)
-        f4 th[V], a[V], b[V];
+        // the piece in columns relative to the chunk's first one (fits 32 bits once clamped)
+        const long long lo_c = lo - c0, hi_c = hi - c0;
+        lo_rel = lo_c < -8 ? -8 : (int)lo_c;
+        hi_rel = hi_c > CH + 8 ? (int)(CH + 8) : (int)hi_c;
+        e_bytes = (uintptr_t)((c0 - lo) * 4);        // byte offset of the piece's (virtual) element at column c0
+      };
+      constexpr int H = BSGD_PIECE_WIDTH(V);
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          th[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.theta + e_first) + toff[v]);
-          if constexpr (MODE >= kMomentum) a[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.s0 + e_first) + toff[v]);
-          if constexpr (MODE == kRmspropMom) b[v] = *reinterpret_cast<const f4u*>(reinterpret_cast<const char*>(seg.s1 + e_first) + toff[v]);
+      for (int v0 = 0; v0 < V; v0 += H) {
+        f4 th[H], a[H], b[H];
+        if constexpr (MODE != kClipReduce) {
+#pragma unroll 1
+          for (int pj = j0; pj <= j1; ++pj) {
+            Segment sg; int lo_rel, hi_rel; uintptr_t e_bytes;
+            piece(pj, sg, lo_rel, hi_rel, e_bytes);
+            if (sg.theta == nullptr) continue;         // a gap
+#pragma unroll
+            for (int i = 0; i < H; ++i) {
+              const int rel = 4 * S::group_of(v0 + i);
+              if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
+                th[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]);
+                if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]);
+                if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]);
+              }
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < H; ++i) update_vec<MODE>(g[v0 + i], th[i], a[i], b[i], p);   // lanes that own nothing: not stored
         }
+#pragma unroll 1
+        for (int pj = j0; pj <= j1; ++pj) {
+          Segment sg; int lo_rel, hi_rel; uintptr_t e_bytes;
+          piece(pj, sg, lo_rel, hi_rel, e_bytes);
+          if (sg.theta == nullptr) continue;           // a gap
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          update_vec<MODE>(g[v], th[v], a[v], b[v], p);
-          *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.theta + e_first) + toff[v]) = th[v];
-          if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.s0 + e_first) + toff[v]) = a[v];
-          if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<char*>(seg.s1 + e_first) + toff[v]) = b[v];
+          for (int i = 0; i < H; ++i) {
+            const int rel = 4 * S::group_of(v0 + i);
+            if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
+              done |= 1u << (v0 + i);
+              if constexpr (MODE == kClipReduce) {
+                const f4 x = g[v0 + i];
+                sumsq = fmaf(x.x, x.x, sumsq);
+                sumsq = fmaf(x.y, x.y, sumsq);
+                sumsq = fmaf(x.z, x.z, sumsq);
+                sumsq = fmaf(x.w, x.w, sumsq);
+              } else {
+                *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]) = th[i];
+                if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]) = a[i];
+                if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]) = b[i];
+              }
+            }
+          }
         }
       }
-    } else {
-      // ---- the chunk holds a tensor boundary, a gap, or the end of the row ---------------
-      // One group after the other (this path is rare; it favours few registers
-      // over loads in flight).
+      // Groups cut by a piece boundary (or lying in a gap), one per boundary
+      // that is not a multiple of 4: element by element, but with the four
+      // elements' look-ups, loads and stores each issued together.
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         const long long gcol = c0 + 4LL * S::group_of(v);
-        if (gcol >= span_end4) continue;
-        const f4 gv = g[v];
-        if constexpr (MODE == kClipReduce) {
-          // the stored mean is laid out like a row: whole groups, gaps included
-          *reinterpret_cast<f4*>(p.gbar + gcol) = gv;
-        }
-        if (gcol + 4 <= p.col_lo || gcol >= p.col_hi) continue;
-        // segment of the group's first covered column
-        int j = 0;
-        long long s_start = p.col_lo, s_end = p.col_hi;
-        Segment sg = seg;
-        if constexpr (MULTI) {
-          const long long x = gcol < p.col_lo ? p.col_lo : gcol;
-          j = find_segment(starts_lds, p.S, (unsigned)x);
-          s_start = starts_lds[j];
-          s_end = starts_lds[j + 1];
-          sg = p.table[j];
-        }
-        if (gcol >= s_start && gcol + 4 <= s_end) {
-          // whole group inside one segment
-          if (sg.theta == nullptr) continue;           // a gap
-          if constexpr (MODE == kClipReduce) {
-            sumsq = fmaf(gv.x, gv.x, sumsq);
-            sumsq = fmaf(gv.y, gv.y, sumsq);
-            sumsq = fmaf(gv.z, gv.z, sumsq);
-            sumsq = fmaf(gv.w, gv.w, sumsq);
-          } else {
-            const long long e = gcol - s_start;
-            f4 th, a, b;
-            th = *reinterpret_cast<const f4u*>(sg.theta + e);
-            if constexpr (MODE >= kMomentum) a = *reinterpret_cast<const f4u*>(sg.s0 + e);
-            if constexpr (MODE == kRmspropMom) b = *reinterpret_cast<const f4u*>(sg.s1 + e);
-            update_vec<MODE>(gv, th, a, b, p);
-            *reinterpret_cast<f4u*>(sg.theta + e) = th;
-            if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(sg.s0 + e) = a;
-            if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(sg.s1 + e) = b;
-          }
-        } else {
-          // the group is cut by a boundary: element by element
+        if (((done >> v) & 1u) || !valid[v] || gcol + 4 <= p.col_lo || gcol >= p.col_hi) continue;
+        bool ok[4];
+        int jq[4];
+        long long first_col[4];
+        int j = j0;
+        long long s_start = seg_start, s_end = seg_end;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const long long col = gcol + q;
-            if (col < p.col_lo || col >= p.col_hi) continue;
-            if constexpr (MULTI) {
-              while (col >= s_end) {                   // segments are non-empty: at most 3 steps per group
+        for (int q = 0; q < 4; ++q) {
+          const long long col = gcol + q;
+          ok[q] = col >= p.col_lo && col < p.col_hi;
+          if constexpr (MULTI) {
+            if (ok[q]) {
+              while (col >= s_end) {                   // walk the start columns on from the chunk's first piece
                 ++j;
                 s_start = s_end;
                 s_end = starts_lds[j + 1];
-                sg = p.table[j];
               }
             }
-            if (sg.theta == nullptr) continue;         // a gap
-            const float gq = gv[q];
-            if constexpr (MODE == kClipReduce) {
-              sumsq = fmaf(gq, gq, sumsq);
-            } else {
-              const long long e = col - s_start;
-              float t1 = sg.theta[e], a1 = 0.f, b1 = 0.f;
-              if constexpr (MODE >= kMomentum) a1 = sg.s0[e];
-              if constexpr (MODE == kRmspropMom) b1 = sg.s1[e];
-              update_elem<MODE>(gq, t1, a1, b1, p);
-              sg.theta[e] = t1;
-              if constexpr (MODE >= kMomentum) sg.s0[e] = a1;
-              if constexpr (MODE == kRmspropMom) sg.s1[e] = b1;
+          }
+          jq[q] = j;
+          first_col[q] = s_start;
+        }
+        Segment sq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          sq[q] = seg;
+          if constexpr (MULTI) {
+            if (ok[q]) sq[q] = p.table[jq[q]];
+          }
+          ok[q] = ok[q] && sq[q].theta != nullptr;     // else: a gap
+        }
+        if constexpr (MODE == kClipReduce) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (ok[q]) sumsq = fmaf(g[v][q], g[v][q], sumsq);
+        } else {
+          float t1[4], a1[4], b1[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            t1[q] = a1[q] = b1[q] = 0.f;
+            if (ok[q]) {
+              const long long e = gcol + q - first_col[q];
+              t1[q] = sq[q].theta[e];
+              if constexpr (MODE >= kMomentum) a1[q] = sq[q].s0[e];
+              if constexpr (MODE == kRmspropMom) b1[q] = sq[q].s1[e];
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (ok[q]) {
+              const long long e = gcol + q - first_col[q];
+              update_elem<MODE>(g[v][q], t1[q], a1[q], b1[q], p);
+              sq[q].theta[e] = t1[q];
+              if constexpr (MODE >= kMomentum) sq[q].s0[e] = a1[q];
+              if constexpr (MODE == kRmspropMom) sq[q].s1[e] = b1[q];
             }
           }
         }
@@ -462,9 +572,8 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
     if constexpr (MODE == kClipReduce) {
       const double s = block_sum<BS>(sumsq, red_lds);
       if (threadIdx.x == 0) p.partials[chunk_id] = s;
-      __syncthreads();                                 // red_lds is reused by the next chunk
     }
-  }  // chunk loop
+  }
 }
 
 // One workgroup adds the per-block sums of squares in a fixed order (fp64),
