@@ -52,9 +52,9 @@ struct Variant {
     {k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), true, true>},     \
     {k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), true, true>}, \
     {k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), true, true>}}, \
-   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, 0), true, false>},               \
-    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, 0), true, false>},     \
-    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, 0), true, false>}}}
+   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, NT), true, false>},               \
+    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, NT), true, false>},     \
+    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, NT), true, false>}}}
 
 // Ordered widest chunk first (the automatic choice walks it in order).  A
 // build may supply its own list.
