@@ -67,11 +67,16 @@ def exact_step(grads: Sequence[Sequence[float]], kept: Sequence[int], theta: Lis
                state: Dict[str, List[Fraction]], hyper: Dict) -> None:
     """theta(t+1) from theta(t) and the kept gradients, exactly.  `theta` and
     the lists in `state` ('v' for momentum; 'ms','m' for RMSProp with
-    momentum) are updated in place.  Clipping by the global norm of the mean
+    momentum; 'ema' for the moving average of Algorithm 4's last line) are
+    updated in place.  Clipping by the global norm of the mean
     gradient is applied when hyper['clip_norm'] is positive and finite."""
     N = len(kept)
     P = len(theta)
     lr = Fraction(hyper["lr"])
+    if "ema" in state:                                  # thetabar(t) from theta(t): before the update below
+        al = Fraction(hyper["ema_decay"])
+        for i in range(P):
+            state["ema"][i] = al * state["ema"][i] + (1 - al) * theta[i]
     G = []
     for i in range(P):
         s = Fraction(0)

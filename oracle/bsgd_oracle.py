@@ -18,6 +18,8 @@ What the step is, in the paper's notation:
     optimizer in place of SGD; Appendix A.2/A.3 name RMSProp with momentum.
   * Appendix A.3: clipping scales the gradient by its global norm taken over
     all layers.
+  * Sec. 1.1 and the last line of Algorithm 4: an exponential moving average
+    thetabar of the parameters with decay rate alpha (0.9999 in Appendix A).
 
 Readings where the paper is silent (each is listed in the design notes):
 ties in arrival time go to the lower worker index; an arrival time of +inf
@@ -32,7 +34,7 @@ definition check for the selection, a message-queue simulation of the
 collect loop, the plain mean for b=0, exact rational arithmetic on tiny
 inputs, NaN-poisoned dropped rows, joint permutation of workers, closed-form
 SGD / momentum / RMSProp trajectories for constant gradients, numpy's norm
-for clipping.  No function here is unpinned.
+for clipping, closed forms and exact rational replay for the moving average.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -108,6 +110,14 @@ def clip_scale(gbars: Sequence[np.ndarray], c: float) -> float:
 # ----------------------------------------------------------------------------
 # optimizer updates on the aggregated gradient G (all in place, fp64)
 # ----------------------------------------------------------------------------
+def update_ema(ema: np.ndarray, theta_before: np.ndarray, alpha: float) -> None:
+    """Sec. 1.1 / last line of Algorithm 4: thetabar(t) = alpha thetabar(t-1) +
+    (1 - alpha) theta(t), where theta(t) are the parameters step t starts
+    from (the printed index: the value before this step's update)."""
+    ema *= alpha
+    ema += (1.0 - alpha) * theta_before
+
+
 def update_sgd(theta: np.ndarray, G: np.ndarray, lr: float) -> None:
     """Sec. 1.1: theta(t+1) = theta(t) - gamma_t G(t)."""
     theta -= lr * G
@@ -141,8 +151,9 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
     grads      indexable by worker k -> fp32 row (length >= every offset+numel)
     arrival_t  fp32[N+b]
     tensors    list of dicts: 'theta' fp64[numel] (updated in place), 's0',
-               's1' fp64[numel] or None, 'grad_offset' int
-    hyper      dict: opt, lr, momentum, decay, eps, clip_norm
+               's1' fp64[numel] or None, 'grad_offset' int, optionally 'ema'
+               fp64[numel] (the moving average thetabar, updated in place)
+    hyper      dict: opt, lr, momentum, decay, eps, clip_norm, ema_decay
 
     Returns (ok, sel_idx, t_step).  ok=False (fewer than N arrivals) leaves
     every tensor untouched.
@@ -165,6 +176,8 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
     opt = hyper["opt"]
     lr = float(hyper["lr"])
     for tz, G in zip(tensors, gbars):
+        if tz.get("ema") is not None:                  # uses theta(t), so it comes before the update
+            update_ema(tz["ema"], tz["theta"], float(hyper["ema_decay"]))
         if opt == SGD:
             update_sgd(tz["theta"], G, lr)
         elif opt == MOMENTUM:
