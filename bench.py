@@ -30,10 +30,10 @@ HBM_PEAK_GBS = 8000.0
 STATE_STREAMS = {"sgd": 2, "momentum": 4, "rmsprop_mom": 6}
 
 
-def required_bytes(N: int, P: int, opt: str) -> int:
+def required_bytes(N: int, P: int, opt: str, ema: bool = False) -> int:
     """Algorithmic HBM bytes of one step: N kept rows read once, theta and
-    optimizer state read once and written once."""
-    return (N * P + STATE_STREAMS[opt] * P) * 4
+    optimizer state (and the moving average, if kept) read once and written once."""
+    return (N * P + (STATE_STREAMS[opt] + (2 if ema else 0)) * P) * 4
 
 
 def cpu_baseline(cfg, seconds_target: float = 15.0):
@@ -88,6 +88,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run plain device copies of this many MiB (yardstick for the profiler's HBM counters)")
+    ap.add_argument("--ema-decay", type=float, default=None,
+                    help="also keep the moving average of theta (not part of the headline workload)")
     ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal override for the reduce kernel")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -123,10 +125,14 @@ def main() -> int:
     theta = torch.from_numpy(wl.theta0(cfg)).cuda()
     state = [torch.zeros(P, device="cuda") for _ in range(ns)]
     arrivals = torch.from_numpy(np.stack([wl.arrival_times(cfg, s) for s in range(Wm + 2 * K)])).cuda()
-    items = [(theta[o:o + n], state[0][o:o + n] if ns > 0 else None, state[1][o:o + n] if ns > 1 else None, o, n)
+    use_ema = args.ema_decay is not None
+    ema = theta.clone() if use_ema else None
+    items = [(theta[o:o + n], state[0][o:o + n] if ns > 0 else None, state[1][o:o + n] if ns > 1 else None, o, n,
+              ema[o:o + n] if use_ema else None)
              for o, n in zip(offs, sizes)]
     tensors = bs.make_tensors(items)
-    hyper = bs.make_hyper(cfg.opt, cfg.lr, cfg.momentum, cfg.decay, cfg.eps, cfg.clip_norm)
+    hyper = bs.make_hyper(cfg.opt, cfg.lr, cfg.momentum, cfg.decay, cfg.eps, cfg.clip_norm,
+                          args.ema_decay if use_ema else 0.0)
     ws = bs.alloc_workspace(P, N, b, T, hyper)
     sel = torch.zeros(N, dtype=torch.int32, device="cuda")
     st = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -176,7 +182,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    req = required_bytes(N, P, cfg.opt)
+    req = required_bytes(N, P, cfg.opt, use_ema)
     gbs = req / (ms_per_step * 1e-3) / 1e9
     achieved = (req / launches) / (kernel_ms * 1e-3) / 1e9
 
@@ -194,7 +200,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: P={P} fp32 in {T} tensor(s), N={N} kept of {W} workers, {cfg.opt}"
-                               + (f", clip {cfg.clip_norm}" if cfg.clip_norm > 0 else ""),
+                               + (f", clip {cfg.clip_norm}" if cfg.clip_norm > 0 else "")
+                               + (f", moving average alpha={args.ema_decay}" if use_ema else ""),
                    "P": P, "N": N, "b": b, "T": T, "optimizer": cfg.opt, "ld": ld,
                    "required_bytes_per_step": req},
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),

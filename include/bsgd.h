@@ -15,6 +15,8 @@
  *      Appendix A.2/A.3 use RMSProp with momentum.
  *   3. Optionally the aggregated gradient is first clipped by its global L2
  *      norm over all layers (Appendix A.3 describes global-norm clipping).
+ *   4. Optionally an exponential moving average of theta is kept (Sec. 1.1;
+ *      the last line of Algorithm 4).
  *
  * Conventions for every entry point
  *   - Pointers marked DEVICE are HIP device pointers valid on the current
@@ -66,6 +68,8 @@ typedef struct {
   float   eps;        /* epsilon, added inside the square root (BSGD_RMSPROP_MOM)   */
   float   clip_norm;  /* c: G <- G*min(1, c/||G||_2), norm over all tensors;
                          <= 0, NaN or +inf switches clipping off                    */
+  float   ema_decay;  /* alpha in [0,1] of the moving average of theta (used when
+                         the tensors carry an `ema` buffer)                         */
 } bsgd_hyper;
 
 /* One parameter tensor.  The struct array itself is HOST memory; the
@@ -78,6 +82,11 @@ typedef struct {
   float*  s1;           /* m (BSGD_RMSPROP_MOM); else NULL                          */
   int64_t grad_offset;  /* where this tensor starts inside every gradient row       */
   int64_t numel;        /* >= 0                                                     */
+  float*  ema;          /* thetabar, the exponential moving average of theta (Sec.
+                           1.1; last line of Algorithm 4), or NULL.  Updated as
+                           thetabar <- alpha*thetabar + (1-alpha)*theta(t) from the
+                           value of theta BEFORE this step's update.  Either
+                           every non-empty tensor has one or none has.            */
 } bsgd_tensor;
 
 /* Algorithm 4, collect loop: which N of the N+b gradients are kept.

@@ -29,12 +29,13 @@ _OPT_BY_NAME = {"sgd": BSGD_SGD, "momentum": BSGD_MOMENTUM, "rmsprop_mom": BSGD_
 
 class bsgd_hyper(ctypes.Structure):
     _fields_ = [("opt", ctypes.c_int32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
-                ("decay", ctypes.c_float), ("eps", ctypes.c_float), ("clip_norm", ctypes.c_float)]
+                ("decay", ctypes.c_float), ("eps", ctypes.c_float), ("clip_norm", ctypes.c_float),
+                ("ema_decay", ctypes.c_float)]
 
 
 class bsgd_tensor(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("s0", ctypes.c_void_p), ("s1", ctypes.c_void_p),
-                ("grad_offset", ctypes.c_int64), ("numel", ctypes.c_int64)]
+                ("grad_offset", ctypes.c_int64), ("numel", ctypes.c_int64), ("ema", ctypes.c_void_p)]
 
 
 class BsgdError(RuntimeError):
@@ -124,21 +125,23 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_hyper(opt, lr: float, momentum: float = 0.0, decay: float = 0.0, eps: float = 0.0,
-               clip_norm: float = 0.0) -> bsgd_hyper:
+               clip_norm: float = 0.0, ema_decay: float = 0.0) -> bsgd_hyper:
     code = _OPT_BY_NAME[opt] if isinstance(opt, str) else int(opt)
-    return bsgd_hyper(code, lr, momentum, decay, eps, clip_norm)
+    return bsgd_hyper(code, lr, momentum, decay, eps, clip_norm, ema_decay)
 
 
 def make_tensors(items: Iterable[Tuple[DevPtr, DevPtr, DevPtr, int, int]]):
-    """ctypes array of bsgd_tensor from (theta, s0, s1, grad_offset, numel)."""
+    """ctypes array of bsgd_tensor from (theta, s0, s1, grad_offset, numel[, ema])."""
     items = list(items)
     arr = (bsgd_tensor * len(items))()
-    for d, (theta, s0, s1, off, numel) in zip(arr, items):
+    for d, item in zip(arr, items):
+        theta, s0, s1, off, numel = item[:5]
         d.theta = _ptr(theta, torch.float32, "theta")
         d.s0 = _ptr(s0, torch.float32, "s0")
         d.s1 = _ptr(s1, torch.float32, "s1")
         d.grad_offset = int(off)
         d.numel = int(numel)
+        d.ema = _ptr(item[5], torch.float32, "ema") if len(item) > 5 else None
     return arr
 
 

@@ -41,27 +41,48 @@ using StepKernel = void (*)(StepParams);
 
 struct Variant {
   int BS, V, U, NT;
-  StepKernel rows[4][2];     // [mode incl. clip-reduce][multi]   gradient from the kept rows
-  StepKernel apply[3][2];    // [mode][multi]                      gradient from the stored mean
+  StepKernel rows[3][2][2];  // [mode][multi][ema]   gradient from the kept rows, fused update
+  StepKernel reduce[2];      // [multi]              clipped step, pass 1: mean + sum of squares
+  StepKernel apply[3][2][2]; // [mode][multi][ema]   clipped step, pass 2: gradient from the stored mean
 };
 
-#define BSGD_SHAPE(BS, V, U, NT) Shape<BS, V, U, (NT) != 0>
-#define BSGD_VARIANT(BS, V, U, NT)                                                                           \
-  {BS, V, U, NT,                                                                                        \
-   {{k_step<kSgd, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kSgd, BSGD_SHAPE(BS, V, U, NT), true, true>},               \
-    {k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kMomentum, BSGD_SHAPE(BS, V, U, NT), true, true>},     \
-    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, U, NT), true, true>}, \
-    {k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), false, true>, k_step<kClipReduce, BSGD_SHAPE(BS, V, U, NT), true, true>}}, \
-   {{k_step<kSgd, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kSgd, BSGD_SHAPE(BS, V, 1, NT), true, false>},               \
-    {k_step<kMomentum, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kMomentum, BSGD_SHAPE(BS, V, 1, NT), true, false>},     \
-    {k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, NT), false, false>, k_step<kRmspropMom, BSGD_SHAPE(BS, V, 1, NT), true, false>}}}
+template <int MODE, class SH, bool ROWS>
+struct KernelsOf {                                   // [multi][ema]
+  static constexpr StepKernel single_plain = k_step<MODE, SH, false, ROWS, false>;
+  static constexpr StepKernel single_ema = k_step<MODE, SH, false, ROWS, true>;
+  static constexpr StepKernel multi_plain = k_step<MODE, SH, true, ROWS, false>;
+  static constexpr StepKernel multi_ema = k_step<MODE, SH, true, ROWS, true>;
+};
+
+template <int BS, int V, int U, int NT>
+Variant make_variant() {
+  using R = Shape<BS, V, U, NT != 0>;                // row loop shape
+  using A = Shape<BS, V, 1, NT != 0>;                // pass 2 of a clipped step reads one stored row
+  Variant v{};
+  v.BS = BS; v.V = V; v.U = U; v.NT = NT;
+#define BSGD_FILL(dst, MODE, SH, ROWS)                                   \
+  dst[0][0] = KernelsOf<MODE, SH, ROWS>::single_plain;                   \
+  dst[0][1] = KernelsOf<MODE, SH, ROWS>::single_ema;                     \
+  dst[1][0] = KernelsOf<MODE, SH, ROWS>::multi_plain;                    \
+  dst[1][1] = KernelsOf<MODE, SH, ROWS>::multi_ema;
+  BSGD_FILL(v.rows[kSgd], kSgd, R, true)
+  BSGD_FILL(v.rows[kMomentum], kMomentum, R, true)
+  BSGD_FILL(v.rows[kRmspropMom], kRmspropMom, R, true)
+  BSGD_FILL(v.apply[kSgd], kSgd, A, false)
+  BSGD_FILL(v.apply[kMomentum], kMomentum, A, false)
+  BSGD_FILL(v.apply[kRmspropMom], kRmspropMom, A, false)
+#undef BSGD_FILL
+  v.reduce[0] = k_step<kClipReduce, R, false, true, false>;
+  v.reduce[1] = k_step<kClipReduce, R, true, true, false>;
+  return v;
+}
+#define BSGD_VARIANT(BS, V, U, NT) make_variant<BS, V, U, NT>()
 
 // Ordered widest chunk first (the automatic choice walks it in order).  A
 // build may supply its own list.
 #ifndef BSGD_VARIANT_LIST
-#define BSGD_VARIANT_LIST                                                                      \
-  BSGD_VARIANT(256, 8, 2, 1), BSGD_VARIANT(256, 4, 2, 1), BSGD_VARIANT(256, 2, 4, 1), \
-  BSGD_VARIANT(256, 1, 8, 1), BSGD_VARIANT(256, 8, 2, 0)
+#define BSGD_VARIANT_LIST \
+  BSGD_VARIANT(256, 8, 2, 1), BSGD_VARIANT(256, 4, 2, 1), BSGD_VARIANT(256, 1, 8, 1), BSGD_VARIANT(256, 8, 2, 0)
 #endif
 
 const Variant kVariants[] = {BSGD_VARIANT_LIST};
@@ -203,6 +224,7 @@ struct Plan {
   long long col_lo = 0, col_hi = 0;   // columns covered: [col_lo, col_hi)
   int S = 0;                          // segments (S == 1: `single` is used, the vectors stay empty)
   Segment single{};
+  bool ema = false;                   // every tensor carries a moving average
   std::vector<Segment> segs;
   std::vector<unsigned> starts;       // S + 1 entries
 };
@@ -220,7 +242,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
   if ((reinterpret_cast<uintptr_t>(grads) & 15) != 0 || (ld & 3) != 0) return BSGD_ERR_ARG;
   const int mode = hyper->opt;
   long long span = 0;
-  int live = 0, last_live = -1;
+  int live = 0, last_live = -1, with_ema = 0;
   for (int j = 0; j < T; ++j) {
     const bsgd_tensor& t = tensors[j];
     if (t.numel < 0 || t.grad_offset < 0) return BSGD_ERR_ARG;
@@ -229,10 +251,17 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
     if (mode >= BSGD_MOMENTUM && (t.s0 == nullptr || (reinterpret_cast<uintptr_t>(t.s0) & 3))) return BSGD_ERR_ARG;
     if (mode == BSGD_RMSPROP_MOM && (t.s1 == nullptr || (reinterpret_cast<uintptr_t>(t.s1) & 3))) return BSGD_ERR_ARG;
     if (t.grad_offset > ld - t.numel) return BSGD_ERR_ARG;
+    if (t.ema != nullptr) {
+      if (reinterpret_cast<uintptr_t>(t.ema) & 3) return BSGD_ERR_ARG;
+      ++with_ema;
+    }
     if (t.grad_offset + t.numel > span) span = t.grad_offset + t.numel;
     ++live;
     last_live = j;
   }
+  if (with_ema != 0 && with_ema != live) return BSGD_ERR_ARG;   // all tensors or none
+  if (with_ema != 0 && !(hyper->ema_decay >= 0.0f && hyper->ema_decay <= 1.0f)) return BSGD_ERR_ARG;
+  plan->ema = with_ema != 0;
   if (span >= 0xFFFFFFF0LL) return BSGD_ERR_ARG;       // segment starts are kept as 32-bit columns
   const WsLayout L = layout(span, T, clip_on(hyper));
   if (workspace_bytes < L.total) return BSGD_ERR_ARG;
@@ -242,7 +271,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
   if (live == 1) {
     const bsgd_tensor& t = tensors[last_live];
     plan->S = 1;
-    plan->single = Segment{t.theta, t.s0, t.s1};
+    plan->single = Segment{t.theta, t.s0, t.s1, t.ema};
     plan->col_lo = t.grad_offset;
     plan->col_hi = t.grad_offset + t.numel;
     return BSGD_OK;
@@ -262,10 +291,10 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
     const bsgd_tensor& t = tensors[idx];
     if (t.grad_offset < at) return BSGD_ERR_ARG;       // two tensors claim the same gradient columns
     if (t.grad_offset > at) {                          // a gap
-      plan->segs.push_back(Segment{nullptr, nullptr, nullptr});
+      plan->segs.push_back(Segment{nullptr, nullptr, nullptr, nullptr});
       plan->starts.push_back((unsigned)at);
     }
-    plan->segs.push_back(Segment{t.theta, t.s0, t.s1});
+    plan->segs.push_back(Segment{t.theta, t.s0, t.s1, t.ema});
     plan->starts.push_back((unsigned)t.grad_offset);
     at = t.grad_offset + t.numel;
   }
@@ -296,6 +325,8 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.rho = hyper->decay;
   p.one_minus_rho = (float)(1.0 - (double)hyper->decay);
   p.eps = hyper->eps;
+  p.alpha = hyper->ema_decay;
+  p.one_minus_alpha = (float)(1.0 - (double)hyper->ema_decay);
   p.gbar = reinterpret_cast<float*>(ws + L.gbar_off);
   p.partials = reinterpret_cast<double*>(ws + L.partials_off);
   p.header = reinterpret_cast<const WsHeader*>(ws);
@@ -334,14 +365,15 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
     lds = sizeof(unsigned) * ((size_t)plan.S + 1);
   }
 
-  if (!clip) return launch(var.rows[mode][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+  const int ema = plan.ema ? 1 : 0;
+  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p);
 
-  int rc = launch(var.rows[kClipReduce][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
-  return launch(var.apply[mode][multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,

@@ -50,6 +50,7 @@ struct Segment {
   float* theta;
   float* s0;
   float* s1;
+  float* ema;                // moving average of theta, or null
 };
 
 // Head of the workspace.
@@ -69,6 +70,7 @@ struct StepParams {
   int N;
   float inv_n;
   float lr, mu, rho, one_minus_rho, eps;
+  float alpha, one_minus_alpha;   // decay of the moving average of theta
   // clipped steps
   float* gbar;               // mean gradient, laid out like one gradient row
   double* partials;          // one sum of squares per workgroup
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
 // ---------------------------------------------------------------------------
 // Tensor table
 // ---------------------------------------------------------------------------
-constexpr int kUploadBatch = 128;                    // 128 x 28 bytes of descriptors fit the 4 KiB argument buffer
+constexpr int kUploadBatch = 96;                     // 96 x 36 bytes of descriptors fit the 4 KiB argument buffer
 
 struct UploadArgs {
   int first, count, is_last;
@@ -235,6 +237,16 @@ __device__ __forceinline__ void update_elem(float g, float& th, float& a, float&
   }
 }
 
+// Last line of Algorithm 4: thetabar <- alpha thetabar + (1-alpha) theta(t),
+// with theta(t) the value before this step's update.
+__device__ __forceinline__ float ema_elem(float e, float th_before, const StepParams& p) {
+  return fmaf(p.alpha, e, p.one_minus_alpha * th_before);
+}
+__device__ __forceinline__ void ema_vec(f4& e, const f4& th_before, const StepParams& p) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) e[q] = ema_elem(e[q], th_before[q], p);
+}
+
 template <int MODE>
 __device__ __forceinline__ void update_vec(const f4& g, f4& th, f4& a, f4& b, const StepParams& p) {
 #pragma unroll
@@ -292,10 +304,11 @@ __device__ __forceinline__ void store_state(const f4& v, uintptr_t addr) {
 // update, store; `done` collects which groups were handled.  Base addresses
 // are wave-uniform, lanes add their byte offset.  With kClipReduce the groups
 // only add to the sum of squares.
-template <int MODE, class S, int V0, int VN, int V>
+template <int MODE, bool EMA, class S, int V0, int VN, int V>
 __device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&toff)[V], const bool (&valid)[V],
                                              bool all, int lo_rel, int hi_rel, uintptr_t pth, uintptr_t ps0,
-                                             uintptr_t ps1, unsigned& done, float& sumsq, const StepParams& p) {
+                                             uintptr_t ps1, uintptr_t pe, unsigned& done, float& sumsq,
+                                             const StepParams& p) {
   bool in[VN];
 #pragma unroll
   for (int i = 0; i < VN; ++i) {
@@ -315,18 +328,23 @@ __device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&
       }
     }
   } else {
-    f4 th[VN], a[VN], b[VN];
+    f4 th[VN], a[VN], b[VN], e[VN];
 #pragma unroll
     for (int i = 0; i < VN; ++i) {
       if (in[i]) {
         th[i] = load_state<S::NT>(pth + toff[V0 + i]);
         if constexpr (MODE >= kMomentum) a[i] = load_state<S::NT>(ps0 + toff[V0 + i]);
         if constexpr (MODE == kRmspropMom) b[i] = load_state<S::NT>(ps1 + toff[V0 + i]);
+        if constexpr (EMA) e[i] = load_state<S::NT>(pe + toff[V0 + i]);
       }
     }
 #pragma unroll
     for (int i = 0; i < VN; ++i) {
       if (in[i]) {
+        if constexpr (EMA) {
+          ema_vec(e[i], th[i], p);
+          store_state<S::NT>(e[i], pe + toff[V0 + i]);
+        }
         update_vec<MODE>(g[V0 + i], th[i], a[i], b[i], p);
         store_state<S::NT>(th[i], pth + toff[V0 + i]);
         if constexpr (MODE >= kMomentum) store_state<S::NT>(a[i], ps0 + toff[V0 + i]);
@@ -359,7 +377,7 @@ __device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsig
 // (nearly all of them) takes the uniform path with wave-uniform pointers and
 // float4 accesses (4-byte aligned only, since a tensor may start anywhere in
 // the row); a chunk holding a tensor boundary looks segments up per lane.
-template <int MODE, class S, bool MULTI, bool SRC_ROWS>
+template <int MODE, class S, bool MULTI, bool SRC_ROWS, bool EMA>
 __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
   constexpr int BS = S::BS, V = S::V, U = S::U;
   constexpr bool NT = S::NT;
@@ -446,9 +464,10 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
     if (uniform) {
       // ---- the chunk lies inside one tensor (almost always): every lane, all groups at once ---
       const uintptr_t e_bytes = (uintptr_t)((c0 - seg_start) * 4);
-      piece_update<MODE, S, 0, V>(g, toff, valid, true, 0, 0, reinterpret_cast<uintptr_t>(seg.theta) + e_bytes,
-                                  reinterpret_cast<uintptr_t>(seg.s0) + e_bytes,
-                                  reinterpret_cast<uintptr_t>(seg.s1) + e_bytes, done, sumsq, p);
+      piece_update<MODE, EMA, S, 0, V>(g, toff, valid, true, 0, 0, reinterpret_cast<uintptr_t>(seg.theta) + e_bytes,
+                                       reinterpret_cast<uintptr_t>(seg.s0) + e_bytes,
+                                       reinterpret_cast<uintptr_t>(seg.s1) + e_bytes,
+                                       reinterpret_cast<uintptr_t>(seg.ema) + e_bytes, done, sumsq, p);
     } else {
       // ---- the chunk holds tensor boundaries, gaps or the end of the row -------------------
       // Every group lies in at most one piece, so the pieces' loads can share
@@ -474,7 +493,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
       constexpr int H = BSGD_PIECE_WIDTH(V);
 #pragma unroll
       for (int v0 = 0; v0 < V; v0 += H) {
-        f4 th[H], a[H], b[H];
+        f4 th[H], a[H], b[H], e[H];
         if constexpr (MODE != kClipReduce) {
 #pragma unroll 1
           for (int pj = j0; pj <= j1; ++pj) {
@@ -488,11 +507,15 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
                 th[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]);
                 if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]);
                 if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]);
+                if constexpr (EMA) e[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + e_bytes + toff[v0 + i]);
               }
             }
           }
 #pragma unroll
-          for (int i = 0; i < H; ++i) update_vec<MODE>(g[v0 + i], th[i], a[i], b[i], p);   // lanes that own nothing: not stored
+          for (int i = 0; i < H; ++i) {                // lanes that own nothing: not stored
+            if constexpr (EMA) ema_vec(e[i], th[i], p);
+            update_vec<MODE>(g[v0 + i], th[i], a[i], b[i], p);
+          }
         }
 #pragma unroll 1
         for (int pj = j0; pj <= j1; ++pj) {
@@ -514,6 +537,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
                 *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]) = th[i];
                 if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]) = a[i];
                 if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]) = b[i];
+                if constexpr (EMA) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + e_bytes + toff[v0 + i]) = e[i];
               }
             }
           }
@@ -561,21 +585,23 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
           for (int q = 0; q < 4; ++q)
             if (ok[q]) sumsq = fmaf(g[v][q], g[v][q], sumsq);
         } else {
-          float t1[4], a1[4], b1[4];
+          float t1[4], a1[4], b1[4], e1[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            t1[q] = a1[q] = b1[q] = 0.f;
+            t1[q] = a1[q] = b1[q] = e1[q] = 0.f;
             if (ok[q]) {
               const long long e = gcol + q - first_col[q];
               t1[q] = sq[q].theta[e];
               if constexpr (MODE >= kMomentum) a1[q] = sq[q].s0[e];
               if constexpr (MODE == kRmspropMom) b1[q] = sq[q].s1[e];
+              if constexpr (EMA) e1[q] = sq[q].ema[e];
             }
           }
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             if (ok[q]) {
               const long long e = gcol + q - first_col[q];
+              if constexpr (EMA) sq[q].ema[e] = ema_elem(e1[q], t1[q], p);
               update_elem<MODE>(g[v][q], t1[q], a1[q], b1[q], p);
               sq[q].theta[e] = t1[q];
               if constexpr (MODE >= kMomentum) sq[q].s0[e] = a1[q];

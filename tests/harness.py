@@ -24,11 +24,11 @@ REL_L2_TOL = 1e-6
 ELEM_FACTOR = 8.0 * 2.0 ** -24
 
 
-def hyper_dict(cfg, step: int) -> Dict:
+def hyper_dict(cfg, step: int, ema_decay: float = 0.0) -> Dict:
     """Hyper-parameters as the fp32 values the library receives."""
     f = lambda x: float(np.float32(x))
     return dict(opt=cfg.opt, lr=f(wl.lr_at(cfg, step)), momentum=f(cfg.momentum), decay=f(cfg.decay),
-                eps=f(cfg.eps), clip_norm=f(cfg.clip_norm))
+                eps=f(cfg.eps), clip_norm=f(cfg.clip_norm), ema_decay=f(ema_decay))
 
 
 @dataclass
@@ -47,10 +47,11 @@ def n_state(opt: str) -> int:
 
 def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequence[int]] = None,
                ld_extra: int = 0, separate_allocs: bool = False, use_split_calls: bool = False,
-               verbose: bool = True) -> ParityResult:
+               ema_decay: Optional[float] = None, verbose: bool = True) -> ParityResult:
     """sample_blocks: None = oracle over every element; else the oracle only
     follows those column blocks (valid when clipping is off: the update is
-    element-wise)."""
+    element-wise).  ema_decay: also keep the moving average of theta (started
+    at theta0) on both sides and compare it."""
     import torch
     import paper_1604_00981_amd as bs
 
@@ -68,20 +69,25 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
     th0 = wl.theta0(cfg)
     # device parameters/state: views into flat buffers (tensor starts then are
     # as unaligned as the packed layout makes them) or separate allocations
+    use_ema = ema_decay is not None
+    alpha = ema_decay if use_ema else 0.0
     if separate_allocs:
         th_parts = [torch.from_numpy(th0[o:o + n].copy()).to(dev) for o, n in zip(offs, sizes)]
         s_parts = [[torch.zeros(n, device=dev) for n in sizes] for _ in range(ns)]
+        e_parts = [t.clone() for t in th_parts] if use_ema else None
     else:
         th_flat = torch.from_numpy(th0).to(dev)
         s_flat = [torch.zeros(P, device=dev) for _ in range(ns)]
         th_parts = [th_flat[o:o + n] for o, n in zip(offs, sizes)]
         s_parts = [[s[o:o + n] for o, n in zip(offs, sizes)] for s in s_flat]
+        e_flat = th_flat.clone() if use_ema else None
+        e_parts = [e_flat[o:o + n] for o, n in zip(offs, sizes)] if use_ema else None
     items = []
     for j in range(T):
         items.append((th_parts[j], s_parts[0][j] if ns > 0 else None, s_parts[1][j] if ns > 1 else None,
-                      offs[j], sizes[j]))
+                      offs[j], sizes[j], e_parts[j] if use_ema else None))
     tensors = bs.make_tensors(items)
-    hyper0 = bs.make_hyper(**hyper_dict(cfg, 0))
+    hyper0 = bs.make_hyper(**hyper_dict(cfg, 0, alpha))
     ws = bs.alloc_workspace(P, N, b, T, hyper0)
     grads_dev = torch.zeros((W, ld), dtype=torch.float32, device=dev)
     g_pin = torch.zeros((W, ld), dtype=torch.float32, pin_memory=True)   # page-locked staging for uploads
@@ -94,13 +100,15 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
     if sample_blocks is None:
         cols = None
         otz = [dict(theta=th0[o:o + n].astype(np.float64), s0=np.zeros(n) if ns > 0 else None,
-                    s1=np.zeros(n) if ns > 1 else None, grad_offset=o) for o, n in zip(offs, sizes)]
+                    s1=np.zeros(n) if ns > 1 else None, grad_offset=o,
+                    ema=th0[o:o + n].astype(np.float64) if use_ema else None) for o, n in zip(offs, sizes)]
         n_cmp = P
     else:
         cols = wl.block_columns(cfg, sample_blocks)
         n_cmp = cols.shape[0]
         otz = [dict(theta=th0[cols].astype(np.float64), s0=np.zeros(n_cmp) if ns > 0 else None,
-                    s1=np.zeros(n_cmp) if ns > 1 else None, grad_offset=0)]
+                    s1=np.zeros(n_cmp) if ns > 1 else None, grad_offset=0,
+                    ema=th0[cols].astype(np.float64) if use_ema else None)]
     abs_sum = np.zeros(n_cmp)
     res = ParityResult(steps=steps, P=P, sampled=0 if cols is None else n_cmp)
 
@@ -110,6 +118,10 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
 
     def gpu_state(i: int) -> np.ndarray:
         full = np.concatenate([t.cpu().numpy() for t in s_parts[i]]) if separate_allocs else s_flat[i].cpu().numpy()
+        return full if cols is None else full[cols]
+
+    def gpu_ema() -> np.ndarray:
+        full = np.concatenate([t.cpu().numpy() for t in e_parts]) if separate_allocs else e_flat.cpu().numpy()
         return full if cols is None else full[cols]
 
     def check_bound(tag: str):
@@ -126,7 +138,7 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
         t = wl.arrival_times(cfg, step)
         grads_dev.copy_(g_pin)
         t_dev = torch.from_numpy(t).to(dev)
-        hy = hyper_dict(cfg, step)
+        hy = hyper_dict(cfg, step, alpha)
         hyper = bs.make_hyper(**hy)
         if use_split_calls:
             bs.bsgd_select_first_n(t_dev, N, b, sel_dev, ts_dev, st_dev)
@@ -160,9 +172,10 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
             print(f"  {cfg.name} step {step}: kept set ok, t_step={t_step:.4f}", flush=True)
 
     check_bound(f"after {steps} steps")
-    names = ["theta"] + (["s0"] if ns > 0 else []) + (["s1"] if ns > 1 else [])
+    names = ["theta"] + (["s0"] if ns > 0 else []) + (["s1"] if ns > 1 else []) + (["ema"] if use_ema else [])
     for nm in names:
-        got = (gpu_theta() if nm == "theta" else gpu_state(0 if nm == "s0" else 1)).astype(np.float64)
+        got = (gpu_theta() if nm == "theta" else gpu_ema() if nm == "ema"
+               else gpu_state(0 if nm == "s0" else 1)).astype(np.float64)
         ref = np.concatenate([t[nm] for t in otz])
         den = np.linalg.norm(ref)
         rel = float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got - ref))

@@ -39,8 +39,8 @@ def test_header_constants_match_binding():
     consts = dict(re.findall(r"#define\s+(BSGD_[A-Z_]+)\s+\(?(-?\d+)\)?", text))
     for k, v in consts.items():
         assert getattr(bs, k) == int(v), k
-    assert ctypes.sizeof(bs.bsgd_hyper) == 24
-    assert ctypes.sizeof(bs.bsgd_tensor) == 40
+    assert ctypes.sizeof(bs.bsgd_hyper) == 28
+    assert ctypes.sizeof(bs.bsgd_tensor) == 48
 
 
 def test_strerror():
@@ -117,6 +117,11 @@ def test_host_side_argument_checks_enqueue_nothing():
     big_ws = 1 << 22
     clash = bs.make_tensors([(A, A, A, 50, 100), (A, A, A, 0, 51)])
     assert ru(tensors=clash, T=2, ld=152, nbytes=big_ws) == bs.BSGD_ERR_ARG
+    # a moving average on some tensors only, or a decay outside [0,1], is refused
+    some = bs.make_tensors([(A, A, A, 0, 50, A), (A, A, A, 50, 50)])
+    assert ru(tensors=some, T=2, nbytes=big_ws) == bs.BSGD_ERR_ARG
+    alle = bs.make_tensors([(A, A, A, 0, 100, A)])
+    assert ru(tensors=alle, hyper=bs.make_hyper("rmsprop_mom", 0.1, 0.9, 0.9, 1.0, ema_decay=1.5)) == bs.BSGD_ERR_ARG
     # clipping needs the larger workspace
     hyc = bs.make_hyper("sgd", 0.1, clip_norm=1.0)
     need = bs.bsgd_workspace_bytes(100, 4, 1, 1, hyc)

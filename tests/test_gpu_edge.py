@@ -25,13 +25,14 @@ class Case:
     layout: list of (grad_offset, numel); theta_shift: element offset of every
     tensor's theta/state view inside its own allocation (to misalign them)."""
 
-    def __init__(self, N, b, layout, opt, seed=0, ld=None, theta_shift=0, hyper=None):
+    def __init__(self, N, b, layout, opt, seed=0, ld=None, theta_shift=0, hyper=None, ema=None):
         import torch
         import paper_1604_00981_amd as bs
         self.bs, self.torch = bs, torch
         self.N, self.b, self.W = N, b, N + b
         self.layout, self.opt = layout, opt
-        self.hy = _f32(dict(OPTS[opt], **(hyper or {})))
+        self.hy = _f32(dict(OPTS[opt], ema_decay=(ema or 0.0), **(hyper or {})))
+        self.use_ema = ema is not None
         r = np.random.default_rng(seed)
         self.r = r
         span = max([o + n for o, n in layout] + [0])
@@ -39,6 +40,7 @@ class Case:
         self.ld = ((span + 3) // 4 * 4) if ld is None else ld
         ns = NS[opt]
         self.th, self.s = [], [[] for _ in range(ns)]
+        self.ema = []
         self.otz = []
         for o, n in layout:
             t0 = (r.standard_normal(n) * 0.05).astype(np.float32)
@@ -47,10 +49,16 @@ class Case:
             self.th.append(buf[theta_shift:])
             for i in range(ns):
                 self.s[i].append(torch.zeros(n + theta_shift, device="cuda")[theta_shift:])
+            if self.use_ema:
+                ebuf = torch.zeros(n + theta_shift, device="cuda")
+                ebuf[theta_shift:] = torch.from_numpy(t0).cuda()
+                self.ema.append(ebuf[theta_shift:])
             self.otz.append(dict(theta=t0.astype(np.float64), s0=np.zeros(n) if ns > 0 else None,
-                                 s1=np.zeros(n) if ns > 1 else None, grad_offset=o))
+                                 s1=np.zeros(n) if ns > 1 else None, grad_offset=o,
+                                 ema=t0.astype(np.float64) if self.use_ema else None))
         self.tensors = bs.make_tensors([(self.th[j], self.s[0][j] if ns > 0 else None,
-                                         self.s[1][j] if ns > 1 else None, o, n)
+                                         self.s[1][j] if ns > 1 else None, o, n,
+                                         self.ema[j] if self.use_ema else None)
                                         for j, (o, n) in enumerate(layout)])
         self.hyper = bs.make_hyper(**self.hy)
         self.ws = bs.alloc_workspace(span, N, b, len(layout), self.hyper)
@@ -80,6 +88,8 @@ class Case:
         out = {"theta": np.concatenate([x.cpu().numpy() for x in self.th]) if self.th else np.zeros(0)}
         for i, nm in enumerate(("s0", "s1")[:len(self.s)]):
             out[nm] = np.concatenate([x.cpu().numpy() for x in self.s[i]])
+        if self.use_ema:
+            out["ema"] = np.concatenate([x.cpu().numpy() for x in self.ema])
         return out
 
     def compare(self, tol=1e-6):
@@ -114,6 +124,30 @@ def test_misaligned_tensor_starts(opt, shift, goff):
     for _ in range(2):
         c.both(*c.draw())
     c.compare()
+
+
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "rmsprop_mom"])
+@pytest.mark.parametrize("clip", [0.0, 0.01])
+def test_moving_average_edges(opt, clip):
+    # unaligned tensors, cut groups, a gap; alpha = 0 checks the index (thetabar = theta before the update)
+    layout = [(3, 3001), (3004, 1), (3005, 2050), (5060, 77), (5137, 9000)]
+    for alpha in (0.0, 0.9):
+        c = Case(4, 1, layout, opt, seed=31, theta_shift=1, hyper=dict(clip_norm=clip), ema=alpha)
+        before = None
+        for _ in range(2):
+            before = c.gpu_arrays()["theta"].copy()
+            c.both(*c.draw())
+        c.compare()
+        if alpha == 0.0:
+            assert np.array_equal(c.gpu_arrays()["ema"], before)     # bitwise the pre-update parameters
+    # too few arrivals: the average is left alone as well
+    g, t = c.draw()
+    snap = c.gpu_arrays()
+    t[[0, 1, 2]] = np.inf
+    assert c.both(g, t) == c.bs.BSGD_ERR_TOO_FEW
+    after = c.gpu_arrays()
+    for k in snap:
+        assert np.array_equal(snap[k], after[k]), k
 
 
 def test_tensors_listed_out_of_order_with_gaps():

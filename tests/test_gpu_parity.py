@@ -65,6 +65,37 @@ def test_c5_reduced_clip_then_momentum():
     assert all(0.3 < s < 0.7 for s in res.clip_scales), res.clip_scales     # clipping is active
 
 
+# ---------------------------------------------------------------------------
+# exponential moving average of theta (last line of Algorithm 4)
+# ---------------------------------------------------------------------------
+def test_ema_reduced_c2_paper_decay():
+    res = run_parity(wl.scaled_config("C2", 150_001), ema_decay=0.9999)
+    assert "ema" in res.rel_l2
+
+
+def test_ema_reduced_c1_sgd_fast_decay():
+    run_parity(wl.scaled_config("C1", 70_003), ema_decay=0.5)
+
+
+def test_ema_reduced_c4_multi_tensor():
+    run_parity(wl.scaled_config("C4", 300_000), steps=5, ema_decay=0.9)
+
+
+def test_ema_reduced_c4_separate_allocations():
+    run_parity(wl.scaled_config("C4", 150_000), steps=3, ema_decay=0.99, separate_allocs=True)
+
+
+def test_ema_reduced_c5_clipped():
+    P = 64 * 2051
+    cfg = wl.scaled_config("C5", P, clip_norm=float(np.sqrt(P / 134_217_728)))
+    run_parity(cfg, ema_decay=0.9)
+
+
+def test_ema_full_size_c2_sampled():
+    cfg = wl.get_config("C2")
+    run_parity(cfg, steps=4, sample_blocks=_sample_blocks(cfg, k=3), ema_decay=0.9999)
+
+
 def test_split_calls_equal_the_step():
     run_parity(wl.scaled_config("C2", 50_001), steps=3, use_split_calls=True)
 
