@@ -27,13 +27,19 @@ getcontext().prec = 60
 
 
 def ps_collect(arrival_t: Sequence[float], N: int, step_tag: int = 0,
-               stale: Sequence[Tuple[float, int]] = ()) -> Optional[List[int]]:
+               stale: Sequence[Tuple[float, int]] = (), tags: Optional[Sequence[int]] = None,
+               deadline: float = math.inf, keep_all: bool = False) -> Optional[List[int]]:
     """Run the collect loop of Algorithm 4 for step `step_tag`.
 
     arrival_t[k] is when worker k's message tagged `step_tag` is delivered
     (inf/NaN: never).  `stale` lists extra (time, worker) messages carrying
-    the tag of the previous step.  Returns the kept workers in the order they
-    were kept, or None if the loop would wait forever.
+    the tag of the previous step; `tags[k]`, if given, is the tag worker k's
+    message carries instead of `step_tag`.  With a finite `deadline` the
+    parameter side stops listening at that time; with `keep_all` it keeps
+    every current-step message that came in by then (N is then the fewest it
+    may proceed with).  Returns the kept workers in the order they were
+    kept, or None if the loop would wait forever (or the deadline passes with
+    too few).
     """
     queue: List[Tuple[float, int, int, int]] = []   # (time, worker, seq, tag)
     seq = 0
@@ -41,20 +47,24 @@ def ps_collect(arrival_t: Sequence[float], N: int, step_tag: int = 0,
         t = float(t)
         if math.isnan(t) or t == math.inf:
             continue                                # this message is never delivered
-        heapq.heappush(queue, (t, k, seq, step_tag))
+        heapq.heappush(queue, (t, k, seq, step_tag if tags is None else int(tags[k])))
         seq += 1
     for t, k in stale:
         heapq.heappush(queue, (float(t), int(k), seq, step_tag - 1))
         seq += 1
 
     kept: List[int] = []
-    while len(kept) < N:
+    while keep_all or len(kept) < N:
         if not queue:
-            return None                             # "wait" never returns
-        _, k, _, tag = heapq.heappop(queue)
+            break                                   # "wait" never returns
+        t, k, _, tag = heapq.heappop(queue)
+        if t > deadline:
+            break                                   # stopped listening
         if tag == step_tag:
             kept.append(k)
         # else: drop the gradient
+    if len(kept) < N:
+        return None
     return kept
 
 

@@ -73,6 +73,49 @@ def select_first_n(arrival_t, N: int, b: int):
     return np.array(sorted(kept), dtype=np.int32), np.float32(when[last])
 
 
+def select_ex(arrival_t, N: int, b: int, tags=None, step_tag: int = 0, deadline: float = math.inf,
+              n_min: int = 0):
+    """Selection with Algorithm 4's tag test spelled out and an optional deadline.
+
+    A message is eligible if its tag equals the current step (Algorithm 4:
+    a gradient tagged t' != t is dropped) and it arrives no later than
+    `deadline` (Sec. 6 suggests time-outs in place of backup workers).
+
+      n_min == 0  first-N mode: keep the first N eligible messages by
+                  (time, index); fewer than N eligible -> None.
+      n_min >= 1  deadline mode: keep EVERY eligible message (any number from
+                  n_min to N+b); fewer than n_min -> None.  The update then
+                  divides by the number kept.
+
+    Returns (sel_idx int32 ascending, t_step fp32 = latest kept arrival) or None.
+    """
+    t = np.asarray(arrival_t, dtype=np.float32)
+    W = N + b
+    if N < 1 or b < 0 or t.shape != (W,) or n_min < 0 or n_min > W:
+        raise ValueError("bad selection arguments")
+    dl = float(np.float32(deadline))
+    elig = []
+    for k in range(W):
+        x = float(t[k])
+        if math.isnan(x) or x == math.inf:
+            continue                                    # never arrives
+        if tags is not None and int(tags[k]) != int(step_tag):
+            continue                                    # stale (or foreign) tag: dropped
+        if not (x <= dl):
+            continue                                    # after the deadline
+        elig.append(k)
+    order = sorted(elig, key=lambda k: (float(t[k]), k))
+    if n_min == 0:
+        if len(order) < N:
+            return None
+        kept = order[:N]
+    else:
+        if len(order) < n_min:
+            return None
+        kept = order
+    return np.array(sorted(kept), dtype=np.int32), np.float32(t[kept[-1]])
+
+
 # ----------------------------------------------------------------------------
 # Algorithm 4, update line: the mean of the kept gradients
 # ----------------------------------------------------------------------------
@@ -153,12 +196,17 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
     tensors    list of dicts: 'theta' fp64[numel] (updated in place), 's0',
                's1' fp64[numel] or None, 'grad_offset' int, optionally 'ema'
                fp64[numel] (the moving average thetabar, updated in place)
-    hyper      dict: opt, lr, momentum, decay, eps, clip_norm, ema_decay
+    hyper      dict: opt, lr, momentum, decay, eps, clip_norm, ema_decay; and
+               optionally tags, step_tag, deadline, n_min (see select_ex)
 
     Returns (ok, sel_idx, t_step).  ok=False (fewer than N arrivals) leaves
     every tensor untouched.
     """
-    sel = select_first_n(arrival_t, N, b)
+    if any(k in hyper for k in ("tags", "deadline", "n_min")):
+        sel = select_ex(arrival_t, N, b, hyper.get("tags"), int(hyper.get("step_tag", 0)),
+                        float(hyper.get("deadline", math.inf)), int(hyper.get("n_min", 0)))
+    else:
+        sel = select_first_n(arrival_t, N, b)
     if sel is None:
         return False, None, None
     sel_idx, t_step = sel
