@@ -106,6 +106,31 @@ typedef struct {
 int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b,
                         int32_t* sel_idx, float* t_step, int32_t* status, void* stream);
 
+/* Selection with Algorithm 4's tag test spelled out and an optional deadline.
+ * HOST struct; `tags` inside is a DEVICE pointer.
+ *
+ * A message is eligible when its tag equals the current step (Algorithm 4
+ * drops a gradient tagged t' != t: the previous step's stragglers), when it
+ * arrives no later than `deadline` (Sec. 6 proposes time-outs in place of
+ * backup workers), and when its arrival time is neither +inf nor NaN. */
+typedef struct {
+  const int32_t* tags;  /* DEVICE int32[N+b]: step tag of each message; NULL = all current */
+  int32_t step_tag;     /* t, the step being collected                                 */
+  float   deadline;     /* tau; +inf = no deadline; NaN is refused                     */
+  int32_t n_min;        /* 0: keep the first N eligible messages (fewer than N eligible
+                           = BSGD_ERR_TOO_FEW).  >= 1: keep EVERY eligible message,
+                           any number from n_min to N+b (fewer than n_min =
+                           BSGD_ERR_TOO_FEW); the mean then divides by the number kept */
+} bsgd_select_opts;
+
+/* As bsgd_select_first_n, under `opts`.
+ *   sel_idx  DEVICE out int32[N+b] (up to N+b workers can be kept when n_min >= 1)
+ *   n_kept   DEVICE out int32: how many were kept (0 on BSGD_ERR_TOO_FEW); may be
+ *            NULL only when n_min == 0
+ *   t_step   arrival time of the last kept message                              */
+int bsgd_select_ex(const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts,
+                   int32_t* sel_idx, int32_t* n_kept, float* t_step, int32_t* status, void* stream);
+
 /* Algorithm 4, update line, for an already chosen set: sum the N kept rows,
  * take the mean, optionally clip, apply one optimizer update to every tensor.
  *
@@ -139,6 +164,14 @@ int bsgd_step(const float* grads, int64_t ld,
               const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
               void* workspace, size_t workspace_bytes, void* stream);
 
+/* bsgd_step with the selection taken under `opts` (tags, deadline).  With
+ * opts->n_min >= 1 the number of kept gradients is decided on the device and
+ * the mean divides by it (see bsgd_last_kept_count). */
+int bsgd_step_ex(const float* grads, int64_t ld,
+                 const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts,
+                 const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace bsgd_step / bsgd_reduce_update need.  span = the largest
  * grad_offset + numel over the tensors (the total parameter count when the
  * tensors are packed back to back).  Returns 0 for invalid arguments. */
@@ -149,6 +182,10 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
  *   status_out  HOST int32: BSGD_OK or BSGD_ERR_TOO_FEW
  *   t_step_out  HOST fp32: arrival time of the N-th kept gradient          */
 int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out);
+
+/* Synchronises `stream`, then reports how many gradients the last bsgd_step /
+ * bsgd_step_ex on this workspace kept (HOST out). */
+int bsgd_last_kept_count(const void* workspace, void* stream, int32_t* n_kept_out);
 
 /* Synchronises `stream`, then copies the N kept worker indices of the last
  * bsgd_step on this workspace to HOST int32[N]. */

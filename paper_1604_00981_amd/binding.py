@@ -38,6 +38,11 @@ class bsgd_tensor(ctypes.Structure):
                 ("grad_offset", ctypes.c_int64), ("numel", ctypes.c_int64), ("ema", ctypes.c_void_p)]
 
 
+class bsgd_select_opts(ctypes.Structure):
+    _fields_ = [("tags", ctypes.c_void_p), ("step_tag", ctypes.c_int32), ("deadline", ctypes.c_float),
+                ("n_min", ctypes.c_int32)]
+
+
 class BsgdError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -67,6 +72,13 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_step.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_tensor), i32,
                               ctypes.POINTER(bsgd_hyper), vp, sz, vp]
     lib.bsgd_step.restype = ctypes.c_int
+    lib.bsgd_select_ex.argtypes = [vp, i32, i32, ctypes.POINTER(bsgd_select_opts), vp, vp, vp, vp, vp]
+    lib.bsgd_select_ex.restype = ctypes.c_int
+    lib.bsgd_step_ex.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_select_opts), ctypes.POINTER(bsgd_tensor), i32,
+                                 ctypes.POINTER(bsgd_hyper), vp, sz, vp]
+    lib.bsgd_step_ex.restype = ctypes.c_int
+    lib.bsgd_last_kept_count.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.bsgd_last_kept_count.restype = ctypes.c_int
     lib.bsgd_workspace_bytes.argtypes = [i64, i32, i32, i32, ctypes.POINTER(bsgd_hyper)]
     lib.bsgd_workspace_bytes.restype = sz
     lib.bsgd_last_status.argtypes = [vp, vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float)]
@@ -145,6 +157,11 @@ def make_tensors(items: Iterable[Tuple[DevPtr, DevPtr, DevPtr, int, int]]):
     return arr
 
 
+def make_select_opts(tags: DevPtr = None, step_tag: int = 0, deadline: float = float("inf"), n_min: int = 0):
+    """bsgd_select_opts; keep the tags tensor alive as long as the struct is used."""
+    return bsgd_select_opts(_ptr(tags, torch.int32, "tags"), step_tag, deadline, n_min)
+
+
 def _check(rc: int, where: str) -> None:
     if rc != BSGD_OK:
         raise BsgdError(rc, where)
@@ -159,6 +176,15 @@ def bsgd_select_first_n(arrival_t: DevPtr, N: int, b: int, sel_idx: DevPtr, t_st
     _check(lib.bsgd_select_first_n(_ptr(arrival_t, torch.float32, "arrival_t"), N, b,
                                    _ptr(sel_idx, torch.int32, "sel_idx"), _ptr(t_step, torch.float32, "t_step"),
                                    _ptr(status, torch.int32, "status"), _stream(stream)), "bsgd_select_first_n")
+
+
+def bsgd_select_ex(arrival_t: DevPtr, N: int, b: int, opts: bsgd_select_opts, sel_idx: DevPtr, n_kept: DevPtr,
+                   t_step: DevPtr, status: DevPtr, stream=None) -> None:
+    lib = load_library()
+    _check(lib.bsgd_select_ex(_ptr(arrival_t, torch.float32, "arrival_t"), N, b, ctypes.byref(opts),
+                              _ptr(sel_idx, torch.int32, "sel_idx"), _ptr(n_kept, torch.int32, "n_kept"),
+                              _ptr(t_step, torch.float32, "t_step"), _ptr(status, torch.int32, "status"),
+                              _stream(stream)), "bsgd_select_ex")
 
 
 def _ws(workspace: DevPtr, workspace_bytes: Optional[int]) -> Tuple[int, int]:
@@ -185,6 +211,22 @@ def bsgd_step(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, tensors
     ws, nbytes = _ws(workspace, workspace_bytes)
     _check(lib.bsgd_step(_ptr(grads, torch.float32, "grads"), ld, _ptr(arrival_t, torch.float32, "arrival_t"),
                          N, b, tensors, len(tensors), ctypes.byref(hyper), ws, nbytes, _stream(stream)), "bsgd_step")
+
+
+def bsgd_step_ex(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, opts: bsgd_select_opts, tensors,
+                 hyper: bsgd_hyper, workspace: DevPtr, workspace_bytes: Optional[int] = None, stream=None) -> None:
+    lib = load_library()
+    ws, nbytes = _ws(workspace, workspace_bytes)
+    _check(lib.bsgd_step_ex(_ptr(grads, torch.float32, "grads"), ld, _ptr(arrival_t, torch.float32, "arrival_t"),
+                            N, b, ctypes.byref(opts), tensors, len(tensors), ctypes.byref(hyper), ws, nbytes,
+                            _stream(stream)), "bsgd_step_ex")
+
+
+def bsgd_last_kept_count(workspace: DevPtr, stream=None) -> int:
+    n = ctypes.c_int32(0)
+    _check(load_library().bsgd_last_kept_count(_ptr(workspace, None, "workspace"), _stream(stream), ctypes.byref(n)),
+           "bsgd_last_kept_count")
+    return n.value
 
 
 def bsgd_workspace_bytes(span: int, N: int, b: int, T: int, hyper: bsgd_hyper) -> int:

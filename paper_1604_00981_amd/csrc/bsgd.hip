@@ -202,12 +202,30 @@ bool check_select_args(const float* arrival_t, int N, int b) {
 
 extern "C" {
 
+static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts,
+                          int32_t* sel_idx, int32_t* n_kept, float* t_step, int32_t* status, hipStream_t stream) {
+  SelectOpts o{nullptr, 0, INFINITY, 0};
+  if (opts != nullptr) {
+    if (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline) return BSGD_ERR_ARG;
+    o = SelectOpts{opts->tags, opts->step_tag, opts->deadline, opts->n_min};
+  }
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(64), 0, stream, arrival_t, (int)N, (int)(N + b), o, (int*)sel_idx,
+                     (int*)n_kept, t_step, (int*)status);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
 int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b, int32_t* sel_idx, float* t_step,
                         int32_t* status, void* stream) {
   if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr) return BSGD_ERR_ARG;
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(64), 0, (hipStream_t)stream, arrival_t, (int)N, (int)(N + b),
-                     (int*)sel_idx, t_step, (int*)status);
-  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+  return enqueue_select(arrival_t, N, b, nullptr, sel_idx, nullptr, t_step, status, (hipStream_t)stream);
+}
+
+int bsgd_select_ex(const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts, int32_t* sel_idx,
+                   int32_t* n_kept, float* t_step, int32_t* status, void* stream) {
+  if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr || opts == nullptr)
+    return BSGD_ERR_ARG;
+  if (opts->n_min > 0 && n_kept == nullptr) return BSGD_ERR_ARG;   // the count is the only way to know how many
+  return enqueue_select(arrival_t, N, b, opts, sel_idx, n_kept, t_step, status, (hipStream_t)stream);
 }
 
 size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const bsgd_hyper* hyper) {
@@ -305,7 +323,8 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
 }
 
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
-                          int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream) {
+                          const int32_t* n_dev, int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan,
+                          hipStream_t stream) {
   t_last_launches = 0;
   if (plan.S == 0) return BSGD_OK;
   const int mode = hyper->opt;
@@ -320,6 +339,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.status = status;
   p.N = N;
   p.inv_n = 1.0f / (float)N;
+  p.n_dev = n_dev;
   p.lr = hyper->lr;
   p.mu = hyper->momentum;
   p.rho = hyper->decay;
@@ -383,22 +403,39 @@ int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, c
   Plan plan;
   int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel_idx, status, N, T, hyper, workspace, plan, (hipStream_t)stream);
+  return enqueue_update(grads, ld, sel_idx, status, N, nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
+}
+
+static int step_common(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
+                       const bsgd_select_opts* opts, const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
+  if (opts != nullptr && (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline)) return BSGD_ERR_ARG;
+  Plan plan;
+  // in deadline mode up to N+b rows may be kept
+  const bool all_in_time = opts != nullptr && opts->n_min > 0;
+  int rc = make_plan(grads, ld, all_in_time ? N + b : N, tensors, T, hyper, workspace, workspace_bytes, &plan);
+  if (rc != BSGD_OK) return rc;
+  char* ws = static_cast<char*>(workspace);
+  WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
+  int* sel = reinterpret_cast<int*>(ws + kAlign);
+  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->t_step, &hdr->status, (hipStream_t)stream);
+  if (rc != BSGD_OK) return rc;
+  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? &hdr->n_kept : nullptr, T, hyper, workspace,
+                        plan, (hipStream_t)stream);
 }
 
 int bsgd_step(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
               const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, void* workspace,
               size_t workspace_bytes, void* stream) {
-  if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
-  Plan plan;
-  int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
-  if (rc != BSGD_OK) return rc;
-  char* ws = static_cast<char*>(workspace);
-  WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
-  int* sel = reinterpret_cast<int*>(ws + kAlign);
-  rc = bsgd_select_first_n(arrival_t, N, b, sel, &hdr->t_step, &hdr->status, stream);
-  if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel, &hdr->status, N, T, hyper, workspace, plan, (hipStream_t)stream);
+  return step_common(grads, ld, arrival_t, N, b, nullptr, tensors, T, hyper, workspace, workspace_bytes, stream);
+}
+
+int bsgd_step_ex(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
+                 const bsgd_select_opts* opts, const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (opts == nullptr) return BSGD_ERR_ARG;
+  return step_common(grads, ld, arrival_t, N, b, opts, tensors, T, hyper, workspace, workspace_bytes, stream);
 }
 
 int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out) {
@@ -408,6 +445,15 @@ int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, f
   if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
   if (status_out) *status_out = h.status;
   if (t_step_out) *t_step_out = h.t_step;
+  return BSGD_OK;
+}
+
+int bsgd_last_kept_count(const void* workspace, void* stream, int32_t* n_kept_out) {
+  if (workspace == nullptr || n_kept_out == nullptr) return BSGD_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BSGD_ERR_HIP;
+  WsHeader h;
+  if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
+  *n_kept_out = h.n_kept;
   return BSGD_OK;
 }
 

@@ -58,7 +58,7 @@ struct WsHeader {
   int status;          // BSGD_OK or BSGD_ERR_TOO_FEW
   float t_step;        // arrival time of the N-th kept gradient
   float clip_scale;    // min(1, c/||G||)
-  int pad;
+  int n_kept;          // how many gradients the step kept
   double norm;         // ||G|| before clipping
 };
 
@@ -69,6 +69,7 @@ struct StepParams {
   const int* status;         // may be null
   int N;
   float inv_n;
+  const int* n_dev;          // when set: the number of kept rows is read from here (deadline mode)
   float lr, mu, rho, one_minus_rho, eps;
   float alpha, one_minus_alpha;   // decay of the moving average of theta
   // clipped steps
@@ -100,31 +101,49 @@ __device__ __forceinline__ unsigned ordered_time_bits(float t) {
 
 constexpr unsigned kNeverArrives = 0xFF800000u;       // ordered bits of +inf; NaN is above
 
+// Options of the selection (all wave-uniform).
+struct SelectOpts {
+  const int* tags;     // step tag carried by each message, or null
+  int step_tag;        // messages with another tag are dropped (Algorithm 4's tag test)
+  float deadline;      // messages arriving later are dropped; +inf: none
+  int n_min;           // 0: keep the first N eligible; >= 1: keep every eligible one, at least n_min
+};
+
 // One wavefront.  Worker w = lane + 64*r sits in slot r of its lane; its key
 // is (ordered time << 32) | w, so keys are distinct and ties in time go to
-// the lower worker index.  Each key counts how many keys are smaller; the
-// kept set is rank < N.  Output is compacted in ascending worker order with
-// ballots and prefix popcounts.
-__global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival_t, int N, int W,
-                                                int* __restrict__ sel_idx, float* __restrict__ t_step,
-                                                int* __restrict__ status) {
+// the lower worker index.  A message that is not eligible (wrong tag, past
+// the deadline, +inf or NaN time) gets the "never arrives" time.  Each key
+// counts how many keys are smaller; the kept set is rank < K, where K = N, or
+// the number of eligible messages in deadline mode.  Output is compacted in
+// ascending worker order with ballots and prefix popcounts.
+__global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival_t, int N, int W, SelectOpts o,
+                                                int* __restrict__ sel_idx, int* __restrict__ n_kept,
+                                                float* __restrict__ t_step, int* __restrict__ status) {
   __shared__ unsigned long long keys[kMaxWorkers];
   const int lane = threadIdx.x;
   constexpr int R = kMaxWorkers / 64;
   unsigned long long key[R];
   float tval[R];
+  int eligible = 0;
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int w = lane + 64 * r;
     tval[r] = 0.0f;
     key[r] = ~0ull;                                   // padding slot: after every real key
+    bool ok = false;
     if (w < W) {
       tval[r] = arrival_t[w];
-      key[r] = ((unsigned long long)ordered_time_bits(tval[r]) << 32) | (unsigned)w;
+      unsigned bits = ordered_time_bits(tval[r]);
+      ok = bits < kNeverArrives && tval[r] <= o.deadline && (o.tags == nullptr || o.tags[w] == o.step_tag);
+      if (!ok) bits = 0xFFFFFFFFu;
+      key[r] = ((unsigned long long)bits << 32) | (unsigned)w;
     }
     keys[w] = key[r];
+    eligible += __popcll(__ballot(ok));
   }
   __syncthreads();
+  const int K = o.n_min > 0 ? eligible : N;            // how many are kept
+  const bool too_few = o.n_min > 0 ? (eligible < o.n_min) : (eligible < N);
 
   int rank[R];
 #pragma unroll
@@ -139,16 +158,16 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int w = lane + 64 * r;
-    const bool keep = (w < W) && (rank[r] < N);
+    const bool keep = (w < W) && (rank[r] < K);
     const unsigned long long mask = __ballot(keep);
     const int pos = base + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
     if (keep) sel_idx[pos] = w;
     base += __popcll(mask);
-    if ((w < W) && rank[r] == N - 1) {                // the N-th arrival decides the step
-      const unsigned hi = (unsigned)(key[r] >> 32);
-      if (t_step) *t_step = tval[r];
-      *status = (hi >= kNeverArrives) ? -2 : 0;
-    }
+    if ((w < W) && rank[r] == K - 1 && t_step) *t_step = tval[r];   // the last kept arrival: how long the step waited
+  }
+  if (lane == 0) {
+    *status = too_few ? -2 : 0;
+    if (n_kept) *n_kept = too_few ? 0 : K;
   }
 }
 
@@ -386,6 +405,8 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
   __shared__ float red_lds[BS / 64];
 
   if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
+  const int n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
+  const float inv_n = p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n;
 
   if constexpr (MULTI) {
     for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
@@ -433,9 +454,9 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
     if constexpr (SRC_ROWS) {
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] = f4{0.f, 0.f, 0.f, 0.f};
-      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, p.N, toff);
+      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, n_rows, toff);
 #pragma unroll
-      for (int v = 0; v < V; ++v) g[v] *= p.inv_n;
+      for (int v = 0; v < V; ++v) g[v] *= inv_n;
     } else {
 #pragma unroll
       for (int v = 0; v < V; ++v)

@@ -122,6 +122,14 @@ def test_host_side_argument_checks_enqueue_nothing():
     assert ru(tensors=some, T=2, nbytes=big_ws) == bs.BSGD_ERR_ARG
     alle = bs.make_tensors([(A, A, A, 0, 100, A)])
     assert ru(tensors=alle, hyper=bs.make_hyper("rmsprop_mom", 0.1, 0.9, 0.9, 1.0, ema_decay=1.5)) == bs.BSGD_ERR_ARG
+    # selection options: NaN deadline, n_min out of range
+    so = bs.make_select_opts(None, 0, float('nan'), 0)
+    assert lib.bsgd_select_ex(A, 4, 1, ctypes.byref(so), A, A, A, A, None) == bs.BSGD_ERR_ARG
+    so = bs.make_select_opts(None, 0, 1.0, 6)
+    assert lib.bsgd_select_ex(A, 4, 1, ctypes.byref(so), A, A, A, A, None) == bs.BSGD_ERR_ARG
+    so = bs.make_select_opts(None, 0, 1.0, 2)
+    assert lib.bsgd_select_ex(A, 4, 1, ctypes.byref(so), A, None, A, A, None) == bs.BSGD_ERR_ARG   # count needed
+    assert lib.bsgd_step_ex(A, 100, A, 4, 1, None, tz, 1, ctypes.byref(hy), A, ok_ws, None) == bs.BSGD_ERR_ARG
     # clipping needs the larger workspace
     hyc = bs.make_hyper("sgd", 0.1, clip_norm=1.0)
     need = bs.bsgd_workspace_bytes(100, 4, 1, 1, hyc)
