@@ -87,11 +87,18 @@ def exact_step(grads: Sequence[Sequence[float]], kept: Sequence[int], theta: Lis
         al = Fraction(hyper["ema_decay"])
         for i in range(P):
             state["ema"][i] = al * state["ema"][i] + (1 - al) * theta[i]
+    wc = float(hyper.get("worker_clip_norm", 0.0))
+    scale = {k: Fraction(1) for k in kept}
+    if wc > 0.0 and not math.isinf(wc):                 # Appendix A.3: each worker clips its own gradient
+        for k in kept:
+            sq = sum((Fraction(float(grads[k][i])) ** 2 for i in range(P)), Fraction(0))
+            if sq > Fraction(wc) * Fraction(wc):
+                scale[k] = Fraction(wc) / _sqrt_fraction(sq)
     G = []
     for i in range(P):
         s = Fraction(0)
         for k in kept:
-            s += Fraction(float(grads[k][i]))
+            s += scale[k] * Fraction(float(grads[k][i]))
         G.append(s / N)
 
     c = float(hyper.get("clip_norm", 0.0))

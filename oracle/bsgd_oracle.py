@@ -150,6 +150,34 @@ def clip_scale(gbars: Sequence[np.ndarray], c: float) -> float:
     return c / nrm
 
 
+def worker_clip_scales(grads, sel_idx: Sequence[int], ranges: Sequence[Tuple[int, int]], c: float) -> np.ndarray:
+    """Appendix A.3 as printed: every worker collects its gradient across all
+    layers, computes the global norm ||G_k|| and clips its own gradient.
+    Returns, for each kept worker, min(1, c/||G_k||) with the norm taken over
+    the columns in `ranges` (the tensors); 1 when c is not positive and finite."""
+    out = np.ones(len(sel_idx))
+    if not (c > 0.0) or math.isinf(c):
+        return out
+    for i, k in enumerate(sel_idx):
+        sq = 0.0
+        for lo, hi in ranges:
+            r = np.asarray(grads[int(k)][lo:hi], dtype=np.float64)
+            sq += float(np.dot(r, r))
+        nrm = math.sqrt(sq)
+        if nrm > c:
+            out[i] = c / nrm
+    return out
+
+
+def reduce_mean_scaled(grads, sel_idx: Sequence[int], scales: Sequence[float], lo: int, hi: int) -> np.ndarray:
+    """(1/N) * sum over kept workers k of scale_k * G_k[lo:hi], in fp64."""
+    acc = None
+    for k, sc in zip(sel_idx, scales):
+        row = np.asarray(grads[int(k)][lo:hi], dtype=np.float64) * float(sc)
+        acc = row if acc is None else acc + row
+    return acc / len(sel_idx)
+
+
 # ----------------------------------------------------------------------------
 # optimizer updates on the aggregated gradient G (all in place, fp64)
 # ----------------------------------------------------------------------------
@@ -196,7 +224,8 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
     tensors    list of dicts: 'theta' fp64[numel] (updated in place), 's0',
                's1' fp64[numel] or None, 'grad_offset' int, optionally 'ema'
                fp64[numel] (the moving average thetabar, updated in place)
-    hyper      dict: opt, lr, momentum, decay, eps, clip_norm, ema_decay; and
+    hyper      dict: opt, lr, momentum, decay, eps, clip_norm, worker_clip_norm,
+               ema_decay; and
                optionally tags, step_tag, deadline, n_min (see select_ex)
 
     Returns (ok, sel_idx, t_step).  ok=False (fewer than N arrivals) leaves
@@ -211,11 +240,13 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
         return False, None, None
     sel_idx, t_step = sel
 
-    gbars = []
-    for tz in tensors:
-        o = int(tz["grad_offset"])
-        n = tz["theta"].shape[0]
-        gbars.append(reduce_mean(grads, sel_idx, o, o + n))
+    ranges = [(int(tz["grad_offset"]), int(tz["grad_offset"]) + tz["theta"].shape[0]) for tz in tensors]
+    wc = float(hyper.get("worker_clip_norm", 0.0))
+    if wc > 0.0 and not math.isinf(wc):                 # each worker's own clip comes first
+        scales = worker_clip_scales(grads, sel_idx, ranges, wc)
+        gbars = [reduce_mean_scaled(grads, sel_idx, scales, lo, hi) for lo, hi in ranges]
+    else:
+        gbars = [reduce_mean(grads, sel_idx, lo, hi) for lo, hi in ranges]
 
     s = clip_scale(gbars, float(hyper.get("clip_norm", 0.0)))
     if s != 1.0:
