@@ -30,10 +30,11 @@ HBM_PEAK_GBS = 8000.0
 STATE_STREAMS = {"sgd": 2, "momentum": 4, "rmsprop_mom": 6}
 
 
-def required_bytes(N: int, P: int, opt: str, ema: bool = False) -> int:
-    """Algorithmic HBM bytes of one step: N kept rows read once, theta and
-    optimizer state (and the moving average, if kept) read once and written once."""
-    return (N * P + (STATE_STREAMS[opt] + (2 if ema else 0)) * P) * 4
+def required_bytes(N: int, P: int, opt: str, ema: bool = False, worker_clip: bool = False) -> int:
+    """Algorithmic HBM bytes of one step: N kept rows read once (twice with
+    per-worker clipping: norms first), theta and optimizer state (and the
+    moving average, if kept) read once and written once."""
+    return ((2 if worker_clip else 1) * N * P + (STATE_STREAMS[opt] + (2 if ema else 0)) * P) * 4
 
 
 def cpu_baseline(cfg, seconds_target: float = 15.0):
@@ -90,6 +91,8 @@ def main() -> int:
                     help="also run plain device copies of this many MiB (yardstick for the profiler's HBM counters)")
     ap.add_argument("--ema-decay", type=float, default=None,
                     help="also keep the moving average of theta (not part of the headline workload)")
+    ap.add_argument("--worker-clip", type=float, default=0.0,
+                    help="also clip every kept gradient by its own norm (not part of the headline workload)")
     ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal override for the reduce kernel")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -132,7 +135,7 @@ def main() -> int:
              for o, n in zip(offs, sizes)]
     tensors = bs.make_tensors(items)
     hyper = bs.make_hyper(cfg.opt, cfg.lr, cfg.momentum, cfg.decay, cfg.eps, cfg.clip_norm,
-                          args.ema_decay if use_ema else 0.0)
+                          args.ema_decay if use_ema else 0.0, args.worker_clip)
     ws = bs.alloc_workspace(P, N, b, T, hyper)
     sel = torch.zeros(N, dtype=torch.int32, device="cuda")
     st = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -182,7 +185,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    req = required_bytes(N, P, cfg.opt, use_ema)
+    req = required_bytes(N, P, cfg.opt, use_ema, args.worker_clip > 0)
     gbs = req / (ms_per_step * 1e-3) / 1e9
     achieved = (req / launches) / (kernel_ms * 1e-3) / 1e9
 
@@ -201,7 +204,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: P={P} fp32 in {T} tensor(s), N={N} kept of {W} workers, {cfg.opt}"
                                + (f", clip {cfg.clip_norm}" if cfg.clip_norm > 0 else "")
-                               + (f", moving average alpha={args.ema_decay}" if use_ema else ""),
+                               + (f", moving average alpha={args.ema_decay}" if use_ema else "")
+                               + (f", per-worker clip {args.worker_clip}" if args.worker_clip > 0 else ""),
                    "P": P, "N": N, "b": b, "T": T, "optimizer": cfg.opt, "ld": ld,
                    "required_bytes_per_step": req},
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),

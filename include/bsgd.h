@@ -70,6 +70,10 @@ typedef struct {
                          <= 0, NaN or +inf switches clipping off                    */
   float   ema_decay;  /* alpha in [0,1] of the moving average of theta (used when
                          the tensors carry an `ema` buffer)                         */
+  float   worker_clip_norm; /* c_w: every kept gradient is first clipped on its own,
+                         G_k <- G_k*min(1, c_w/||G_k||_2), norm over all tensors
+                         (Appendix A.3 as printed); costs one more pass over the
+                         kept rows; <= 0, NaN or +inf switches it off               */
 } bsgd_hyper;
 
 /* One parameter tensor.  The struct array itself is HOST memory; the

@@ -30,7 +30,7 @@ _OPT_BY_NAME = {"sgd": BSGD_SGD, "momentum": BSGD_MOMENTUM, "rmsprop_mom": BSGD_
 class bsgd_hyper(ctypes.Structure):
     _fields_ = [("opt", ctypes.c_int32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
                 ("decay", ctypes.c_float), ("eps", ctypes.c_float), ("clip_norm", ctypes.c_float),
-                ("ema_decay", ctypes.c_float)]
+                ("ema_decay", ctypes.c_float), ("worker_clip_norm", ctypes.c_float)]
 
 
 class bsgd_tensor(ctypes.Structure):
@@ -137,9 +137,9 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_hyper(opt, lr: float, momentum: float = 0.0, decay: float = 0.0, eps: float = 0.0,
-               clip_norm: float = 0.0, ema_decay: float = 0.0) -> bsgd_hyper:
+               clip_norm: float = 0.0, ema_decay: float = 0.0, worker_clip_norm: float = 0.0) -> bsgd_hyper:
     code = _OPT_BY_NAME[opt] if isinstance(opt, str) else int(opt)
-    return bsgd_hyper(code, lr, momentum, decay, eps, clip_norm, ema_decay)
+    return bsgd_hyper(code, lr, momentum, decay, eps, clip_norm, ema_decay, worker_clip_norm)
 
 
 def make_tensors(items: Iterable[Tuple[DevPtr, DevPtr, DevPtr, int, int]]):

@@ -28,11 +28,14 @@ constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-  size_t sel_off, table_off, starts_off, partials_off, gbar_off, total;
+  size_t sel_off, table_off, starts_off, rowscale_off, rowpart_off, partials_off, gbar_off, total;
   long long max_chunks;
 };
 
 bool clip_on(const bsgd_hyper* h) { return h && h->clip_norm > 0.0f && std::isfinite(h->clip_norm); }
+bool worker_clip_on(const bsgd_hyper* h) {
+  return h && h->worker_clip_norm > 0.0f && std::isfinite(h->worker_clip_norm);
+}
 
 // ---------------------------------------------------------------------------
 // kernel variants (launch shapes)
@@ -43,6 +46,7 @@ struct Variant {
   int BS, V, U, NT;
   StepKernel rows[3][2][2];  // [mode][multi][ema]   gradient from the kept rows, fused update
   StepKernel reduce[2];      // [multi]              clipped step, pass 1: mean + sum of squares
+  StepKernel rowsq[2];       // [multi]              per-worker clipping: per-row sums of squares
   StepKernel apply[3][2][2]; // [mode][multi][ema]   clipped step, pass 2: gradient from the stored mean
 };
 
@@ -74,6 +78,8 @@ Variant make_variant() {
 #undef BSGD_FILL
   v.reduce[0] = k_step<kClipReduce, R, false, true, false>;
   v.reduce[1] = k_step<kClipReduce, R, true, true, false>;
+  v.rowsq[0] = k_row_sumsq<R, false>;
+  v.rowsq[1] = k_row_sumsq<R, true>;
   return v;
 }
 #define BSGD_VARIANT(BS, V, U, NT) make_variant<BS, V, U, NT>()
@@ -99,14 +105,17 @@ long long min_chunk_elems() {
   return m;
 }
 
-WsLayout layout(long long span, int T, bool clip) {
+WsLayout layout(long long span, int T, bool clip, bool worker_clip) {
   WsLayout L{};
   const size_t max_segments = 2 * (size_t)T + 1;      // every tensor may be followed by a gap
   L.sel_off = kAlign;
   L.table_off = L.sel_off + round_up(sizeof(int) * kMaxWorkers, kAlign);
   L.starts_off = L.table_off + round_up(sizeof(Segment) * max_segments, kAlign);
-  L.partials_off = L.starts_off + round_up(sizeof(unsigned) * (max_segments + 1), kAlign);
+  L.rowscale_off = L.starts_off + round_up(sizeof(unsigned) * (max_segments + 1), kAlign);
+  L.rowpart_off = L.rowscale_off + round_up(sizeof(float) * kMaxWorkers, kAlign);
   L.max_chunks = span / min_chunk_elems() + 2;
+  L.partials_off = L.rowpart_off;
+  if (worker_clip) L.partials_off += round_up(sizeof(double) * (size_t)L.max_chunks * kMaxWorkers, kAlign);
   L.gbar_off = L.partials_off;
   L.total = L.partials_off;
   if (clip) {
@@ -232,7 +241,7 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
   if (span < 0 || N < 1 || b < 0 || (long long)N + b > BSGD_MAX_WORKERS || T < 1 || T > BSGD_MAX_TENSORS ||
       hyper == nullptr)
     return 0;
-  return layout(span, T, clip_on(hyper)).total;
+  return layout(span, T, clip_on(hyper), worker_clip_on(hyper)).total;
 }
 
 // What a call will run on: the tensors as sorted, non-overlapping segments of
@@ -281,7 +290,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
   if (with_ema != 0 && !(hyper->ema_decay >= 0.0f && hyper->ema_decay <= 1.0f)) return BSGD_ERR_ARG;
   plan->ema = with_ema != 0;
   if (span >= 0xFFFFFFF0LL) return BSGD_ERR_ARG;       // segment starts are kept as 32-bit columns
-  const WsLayout L = layout(span, T, clip_on(hyper));
+  const WsLayout L = layout(span, T, clip_on(hyper), worker_clip_on(hyper));
   if (workspace_bytes < L.total) return BSGD_ERR_ARG;
   plan->span = span;
   plan->S = 0;
@@ -329,7 +338,8 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   if (plan.S == 0) return BSGD_OK;
   const int mode = hyper->opt;
   const bool clip = clip_on(hyper);
-  const WsLayout L = layout(plan.span, T, clip);
+  const bool wclip = worker_clip_on(hyper);
+  const WsLayout L = layout(plan.span, T, clip, wclip);
   char* ws = static_cast<char*>(workspace);
 
   StepParams p{};
@@ -340,6 +350,10 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.N = N;
   p.inv_n = 1.0f / (float)N;
   p.n_dev = n_dev;
+  p.row_scale = wclip ? reinterpret_cast<const float*>(ws + L.rowscale_off) : nullptr;
+  p.row_partials = reinterpret_cast<double*>(ws + L.rowpart_off);
+  p.n_stride = N;
+  p.worker_clip = hyper->worker_clip_norm;
   p.lr = hyper->lr;
   p.mu = hyper->momentum;
   p.rho = hyper->decay;
@@ -386,6 +400,15 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   }
 
   const int ema = plan.ema ? 1 : 0;
+  if (wclip) {
+    // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
+    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+    if (rc != BSGD_OK) return rc;
+    hipLaunchKernelGGL(k_row_scales, dim3((unsigned)N), dim3(kRowScaleBlock), 0, stream,
+                       (const double*)p.row_partials, (int)total_chunks, (int)N, (int)N, (const int*)n_dev,
+                       hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
+    if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  }
   if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p);
 
   int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);

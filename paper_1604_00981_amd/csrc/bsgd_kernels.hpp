@@ -70,6 +70,10 @@ struct StepParams {
   int N;
   float inv_n;
   const int* n_dev;          // when set: the number of kept rows is read from here (deadline mode)
+  const float* row_scale;    // per kept row: its own clip scale (per-worker clipping), or null
+  double* row_partials;      // [chunk][n_stride]: per chunk and kept row, sum of squares (per-worker clipping)
+  int n_stride;              // rows per chunk in row_partials
+  float worker_clip;         // c of the per-worker clip
   float lr, mu, rho, one_minus_rho, eps;
   float alpha, one_minus_alpha;   // decay of the moving average of theta
   // clipped steps
@@ -208,14 +212,25 @@ __device__ __forceinline__ f4 load_row_f4(const char* rowbase, unsigned byte_off
 // Sum of the kept rows for V float4 columns per thread, rows taken in
 // batches of B so that B*V 16-byte loads are in flight before the first add.
 // Adds happen in ascending row order (fixed, run-to-run identical).
+// acc += scale * r, spelled as one fused multiply-add per component.  With
+// scale == 1 this is exactly acc + r, so the unscaled path keeps its bits.
+__device__ __forceinline__ void fma4(f4& acc, float scale, const f4& r) {
+  acc.x = fmaf(scale, r.x, acc.x);
+  acc.y = fmaf(scale, r.y, acc.y);
+  acc.z = fmaf(scale, r.z, acc.z);
+  acc.w = fmaf(scale, r.w, acc.w);
+}
+
 template <int V, int B, bool NT>
 __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
-                                         long long colbase, const int* __restrict__ sel_idx, int j,
-                                         const unsigned (&toff)[V]) {
+                                         long long colbase, const int* __restrict__ sel_idx,
+                                         const float* __restrict__ row_scale, int j, const unsigned (&toff)[V]) {
   f4 r[B][V];
+  float sc[B];
 #pragma unroll
   for (int u = 0; u < B; ++u) {
     const long long k = sel_idx[j + u];
+    sc[u] = row_scale != nullptr ? row_scale[j + u] : 1.0f;   // per-worker clip scale (wave-uniform)
     const char* rowbase = reinterpret_cast<const char*>(grads + k * ld + colbase);
 #pragma unroll
     for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
@@ -223,20 +238,20 @@ __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__
 #pragma unroll
   for (int u = 0; u < B; ++u)
 #pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] += r[u][v];
+    for (int v = 0; v < V; ++v) fma4(acc[v], sc[u], r[u][v]);
 }
 
 // All kept rows, in batches of U (then 8, 4, 2, 1 for what is left).
 template <int V, int U, bool NT>
 __device__ __forceinline__ void sum_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
-                                         long long colbase, const int* __restrict__ sel_idx, int N,
-                                         const unsigned (&toff)[V]) {
+                                         long long colbase, const int* __restrict__ sel_idx,
+                                         const float* __restrict__ row_scale, int N, const unsigned (&toff)[V]) {
   int j = 0;
-  for (; j + U <= N; j += U) add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, j, toff);
-  if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 8; } }
-  if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 4; } }
-  if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 2; } }
-  if constexpr (U > 1) { if ((N - j) & 1) { add_rows<V, 1, NT>(acc, grads, ld, colbase, sel_idx, j, toff); j += 1; } }
+  for (; j + U <= N; j += U) add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff);
+  if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 8; } }
+  if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 4; } }
+  if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 2; } }
+  if constexpr (U > 1) { if ((N - j) & 1) { add_rows<V, 1, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 1; } }
 }
 
 // The library is compiled with floating-point contraction off and spells its
@@ -454,7 +469,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
     if constexpr (SRC_ROWS) {
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] = f4{0.f, 0.f, 0.f, 0.f};
-      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, n_rows, toff);
+      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, p.row_scale, n_rows, toff);
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] *= inv_n;
     } else {
@@ -637,6 +652,132 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
       const double s = block_sum<BS>(sumsq, red_lds);
       if (threadIdx.x == 0) p.partials[chunk_id] = s;
     }
+  }
+}
+
+// Per-worker clipping (Appendix A.3 as printed), pass A: for this chunk and
+// every kept row, the sum of squares of the row's elements that belong to a
+// tensor.  Same chunking and row order as k_step; rows are read U at a time.
+// Output: row_partials[chunk][row] (fp64), reduced in a fixed order.
+template <class S, bool MULTI>
+__global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p) {
+  constexpr int BS = S::BS, V = S::V, U = S::U;
+  constexpr bool NT = S::NT;
+  constexpr long long CH = 4LL * BS * V;
+  constexpr int WAVES = BS / 64;
+  extern __shared__ unsigned starts_lds[];             // MULTI: starts[S+1]
+  __shared__ float wave_part[kMaxWorkers][WAVES];
+
+  if (p.status != nullptr && *p.status != 0) return;
+  const int n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
+  if constexpr (MULTI) {
+    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
+    __syncthreads();
+  }
+  const long long span_end4 = (p.col_hi + 3) & ~3LL;
+  const int chunk_id = (int)blockIdx.x + p.chunk_base;
+  const long long c0 = p.base + (long long)chunk_id * CH;
+
+  // which of a lane's elements belong to a tensor: 4 bits per group
+  unsigned toff[V];
+  unsigned member[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    const long long gcol = c0 + 4LL * S::group_of(v);
+    toff[v] = gcol < span_end4 ? (unsigned)S::group_of(v) * 16u : 0u;
+    member[v] = 0;
+  }
+  {
+    int j0 = 0, j1 = 0;
+    if constexpr (MULTI) {
+      long long first = c0 < p.col_lo ? p.col_lo : c0;
+      long long last = c0 + CH - 1;
+      if (last >= p.col_hi) last = p.col_hi - 1;
+      if (last < first) last = first;
+      j0 = __builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)first));
+      j1 = __builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)last));
+    }
+#pragma unroll 1
+    for (int pj = j0; pj <= j1; ++pj) {
+      long long lo = p.col_lo, hi = p.col_hi;
+      bool real = true;
+      if constexpr (MULTI) {
+        lo = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj]);
+        hi = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj + 1]);
+        real = p.table[pj].theta != nullptr;
+      }
+      if (!real) continue;
+      const long long lo_c = lo - c0, hi_c = hi - c0;
+      const int lo_rel = lo_c < -8 ? -8 : (int)lo_c;
+      const int hi_rel = hi_c > CH + 8 ? (int)(CH + 8) : (int)hi_c;
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const int rel = 4 * S::group_of(v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (rel + q >= lo_rel && rel + q < hi_rel) member[v] |= 1u << q;
+      }
+    }
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int j = 0; j < n_rows; j += U) {
+    f4 r[U][V];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int jj = j + u < n_rows ? j + u : n_rows - 1;        // a short last batch re-reads the last row
+      const long long k = p.sel_idx[jj];
+      const char* rowbase = reinterpret_cast<const char*>(p.grads + k * p.ld + c0);
+#pragma unroll
+      for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float sq = 0.f;
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float x = ((member[v] >> q) & 1u) ? r[u][v][q] : 0.f;
+          sq = fmaf(x, x, sq);
+        }
+      }
+      sq = wave_sum(sq);
+      if (lane == 0 && j + u < n_rows) wave_part[j + u][wave] = sq;
+    }
+  }
+  __syncthreads();
+  for (int row = threadIdx.x; row < n_rows; row += BS) {
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) s += (double)wave_part[row][w];
+    p.row_partials[(long long)chunk_id * p.n_stride + row] = s;
+  }
+}
+
+// Per-worker clipping, pass B: workgroup `row` adds its row's per-chunk sums
+// in a fixed order (fp64) and writes scale = min(1, c/norm) for that row.
+constexpr int kRowScaleBlock = 256;
+__global__ __launch_bounds__(kRowScaleBlock) void k_row_scales(const double* __restrict__ row_partials, int chunks,
+                                                                int n_stride, int N, const int* __restrict__ n_dev,
+                                                                float c, const int* __restrict__ status,
+                                                                float* __restrict__ row_scale) {
+  __shared__ double red[kRowScaleBlock];
+  if (status != nullptr && *status != 0) return;
+  const int n_rows = n_dev != nullptr ? *n_dev : N;
+  const int row = blockIdx.x;
+  if (row >= n_rows) return;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < chunks; i += kRowScaleBlock) s += row_partials[(long long)i * n_stride + row];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int half = kRowScaleBlock / 2; half > 0; half >>= 1) {
+    if (threadIdx.x < half) red[threadIdx.x] += red[threadIdx.x + half];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double nrm = sqrt(red[0]);
+    row_scale[row] = (nrm <= (double)c) ? 1.0f : (float)((double)c / nrm);
   }
 }
 

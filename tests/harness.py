@@ -24,11 +24,11 @@ REL_L2_TOL = 1e-6
 ELEM_FACTOR = 8.0 * 2.0 ** -24
 
 
-def hyper_dict(cfg, step: int, ema_decay: float = 0.0) -> Dict:
+def hyper_dict(cfg, step: int, ema_decay: float = 0.0, worker_clip: float = 0.0) -> Dict:
     """Hyper-parameters as the fp32 values the library receives."""
     f = lambda x: float(np.float32(x))
     return dict(opt=cfg.opt, lr=f(wl.lr_at(cfg, step)), momentum=f(cfg.momentum), decay=f(cfg.decay),
-                eps=f(cfg.eps), clip_norm=f(cfg.clip_norm), ema_decay=f(ema_decay))
+                eps=f(cfg.eps), clip_norm=f(cfg.clip_norm), ema_decay=f(ema_decay), worker_clip_norm=f(worker_clip))
 
 
 @dataclass
@@ -47,7 +47,7 @@ def n_state(opt: str) -> int:
 
 def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequence[int]] = None,
                ld_extra: int = 0, separate_allocs: bool = False, use_split_calls: bool = False,
-               ema_decay: Optional[float] = None, verbose: bool = True) -> ParityResult:
+               ema_decay: Optional[float] = None, worker_clip: float = 0.0, verbose: bool = True) -> ParityResult:
     """sample_blocks: None = oracle over every element; else the oracle only
     follows those column blocks (valid when clipping is off: the update is
     element-wise).  ema_decay: also keep the moving average of theta (started
@@ -62,7 +62,7 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
     ld = (P + 3) // 4 * 4 + ld_extra
     ns = n_state(cfg.opt)
     clip = cfg.clip_norm > 0
-    if sample_blocks is not None and clip:
+    if sample_blocks is not None and (clip or worker_clip > 0):
         raise ValueError("sampled oracle cannot follow a clipped step")
 
     dev = "cuda"
@@ -87,7 +87,7 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
         items.append((th_parts[j], s_parts[0][j] if ns > 0 else None, s_parts[1][j] if ns > 1 else None,
                       offs[j], sizes[j], e_parts[j] if use_ema else None))
     tensors = bs.make_tensors(items)
-    hyper0 = bs.make_hyper(**hyper_dict(cfg, 0, alpha))
+    hyper0 = bs.make_hyper(**hyper_dict(cfg, 0, alpha, worker_clip))
     ws = bs.alloc_workspace(P, N, b, T, hyper0)
     grads_dev = torch.zeros((W, ld), dtype=torch.float32, device=dev)
     g_pin = torch.zeros((W, ld), dtype=torch.float32, pin_memory=True)   # page-locked staging for uploads
@@ -138,7 +138,7 @@ def run_parity(cfg, steps: Optional[int] = None, sample_blocks: Optional[Sequenc
         t = wl.arrival_times(cfg, step)
         grads_dev.copy_(g_pin)
         t_dev = torch.from_numpy(t).to(dev)
-        hy = hyper_dict(cfg, step, alpha)
+        hy = hyper_dict(cfg, step, alpha, worker_clip)
         hyper = bs.make_hyper(**hy)
         if use_split_calls:
             bs.bsgd_select_first_n(t_dev, N, b, sel_dev, ts_dev, st_dev)

@@ -39,7 +39,7 @@ def test_header_constants_match_binding():
     consts = dict(re.findall(r"#define\s+(BSGD_[A-Z_]+)\s+\(?(-?\d+)\)?", text))
     for k, v in consts.items():
         assert getattr(bs, k) == int(v), k
-    assert ctypes.sizeof(bs.bsgd_hyper) == 28
+    assert ctypes.sizeof(bs.bsgd_hyper) == 32
     assert ctypes.sizeof(bs.bsgd_tensor) == 48
 
 

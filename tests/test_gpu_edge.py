@@ -150,6 +150,63 @@ def test_moving_average_edges(opt, clip):
         assert np.array_equal(snap[k], after[k]), k
 
 
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "rmsprop_mom"])
+@pytest.mark.parametrize("both", [False, True])
+def test_per_worker_clipping(opt, both):
+    # every kept gradient clipped by its own global norm (over tensor columns only), then averaged;
+    # optionally followed by the clip of the mean
+    layout = [(5, 3001), (3006, 1), (3007, 2050), (5070, 77), (5147, 9000)]        # a gap at 5057..5069
+    hy = dict(worker_clip_norm=0.9, clip_norm=0.05 if both else 0.0)
+    c = Case(9, 3, layout, opt, seed=41, theta_shift=1, hyper=hy)
+    for step in range(3):
+        g, t = c.draw(sigma=0.01)
+        g *= c.r.uniform(0.2, 3.0, (c.W, 1)).astype(np.float32)                    # workers of very different norms
+        covered = np.zeros(c.ld, bool)
+        for o, n in layout:
+            covered[o:o + n] = True
+        g[:, ~covered] = 50.0                                                      # gap columns must not enter any norm
+        sel, _ = orc.select_first_n(t, c.N, c.b)
+        sc = orc.worker_clip_scales(g, sel, [(o, o + n) for o, n in layout], c.hy["worker_clip_norm"])
+        assert (sc < 1).any() and (sc == 1).any()                                  # some clipped, some not
+        c.both(g, t)
+    c.compare()
+
+
+def test_per_worker_clipping_off_when_threshold_is_large():
+    a = Case(6, 2, [(0, 7001)], "momentum", seed=42)
+    b = Case(6, 2, [(0, 7001)], "momentum", seed=42, hyper=dict(worker_clip_norm=1e9))
+    for _ in range(2):
+        g, t = a.draw()
+        a.gpu_step(g, t)
+        b.gpu_step(g, t)
+    ga, gb = a.gpu_arrays(), b.gpu_arrays()
+    for k in ga:
+        assert np.array_equal(ga[k], gb[k]), k          # a scale of exactly 1 changes no bit
+
+
+def test_update_in_two_partial_calls_equals_one_call():
+    # top-layer tensors can be updated while lower layers are still arriving (Appendix A.3's pipelining):
+    # a step applied tensor subset by tensor subset gives the same bits as one call
+    import torch
+    layout = [(0, 5000), (5000, 777), (5777, 12001), (17778, 64)]
+    one = Case(7, 2, layout, "rmsprop_mom", seed=43)
+    two = Case(7, 2, layout, "rmsprop_mom", seed=43)
+    bs = one.bs
+    for _ in range(2):
+        g, t = one.draw()
+        one.gpu_step(g, t)
+        g_dev, t_dev = torch.from_numpy(g).cuda(), torch.from_numpy(t).cuda()
+        sel = torch.zeros(7, dtype=torch.int32, device="cuda")
+        st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        bs.bsgd_select_first_n(t_dev, 7, 2, sel, None, st)
+        for part in ([3, 2], [0, 1]):                   # "top layers" first
+            items = [(two.th[j], two.s[0][j], two.s[1][j], layout[j][0], layout[j][1]) for j in part]
+            bs.bsgd_reduce_update(g_dev, two.ld, sel, st, 7, bs.make_tensors(items), two.hyper, two.ws)
+    ga, gb = one.gpu_arrays(), two.gpu_arrays()
+    for k in ga:
+        assert np.array_equal(ga[k], gb[k]), k
+
+
 def test_tensors_listed_out_of_order_with_gaps():
     # descriptors in arbitrary order, holes between tensors, first tensor not at column 0
     layout = [(9000, 2500), (7, 1000), (4001, 3), (1500, 2501), (4100, 4099), (8300, 64)]

@@ -96,6 +96,18 @@ def test_ema_full_size_c2_sampled():
     run_parity(cfg, steps=4, sample_blocks=_sample_blocks(cfg, k=3), ema_decay=0.9999)
 
 
+def test_per_worker_clip_reduced_c2():
+    # gradients ~ s_k * N(0,1e-3^2) over P columns: ||G_k|| ~ s_k*1e-3*sqrt(P), s_k in [0.5,1.5]:
+    # a threshold at the middle clips about half of the workers
+    P = 200_003
+    run_parity(wl.scaled_config("C2", P), steps=6, worker_clip=float(1e-3 * np.sqrt(P)))
+
+
+def test_per_worker_clip_reduced_c4_multi_tensor_and_global_clip():
+    cfg = wl.scaled_config("C4", 300_000, clip_norm=2e-4)
+    run_parity(cfg, steps=4, worker_clip=1.5)
+
+
 def test_split_calls_equal_the_step():
     run_parity(wl.scaled_config("C2", 50_001), steps=3, use_split_calls=True)
 
