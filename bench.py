@@ -69,9 +69,11 @@ def cpu_baseline(cfg, seconds_target: float = 15.0):
     }
 
 
-def measured_traffic():
+def measured_traffic(plain_c2: bool):
     """HBM bytes per launch of the dominant kernel from the committed
-    rocprofv3 counter summary, if one is present."""
+    rocprofv3 counter summary (taken on the plain C2 workload), if present."""
+    if not plain_c2:
+        return None
     p = os.path.join(ROOT, "profiles", "c2_reduce_update_traffic.json")
     try:
         with open(p) as f:
@@ -211,7 +213,7 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "steps_per_s": round(1e3 / ms_per_step, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name == "C2" and not use_ema and args.worker_clip <= 0),
                      "kernel": "k_step (reduce + fused update)", "launches_per_step": launches,
                      "kernel_ms": round(kernel_ms, 5), "kernel_ms_per_step": round(kernel_ms_step, 5),
                      "algorithmic_bytes_per_launch": req // launches},
