@@ -125,6 +125,7 @@ WsLayout layout(long long span, int T, bool clip, bool worker_clip) {
   return L;
 }
 
+constexpr int kApplyRoundsPerLaunch = 8;
 std::atomic<int> g_variant{-1};                      // -1: choose by problem size
 thread_local int t_last_launches = 0;                // reduce/update launches of this thread's last call
 
@@ -178,17 +179,19 @@ long long round_size(StepKernel fn, int block, size_t lds) {
 }
 
 // Enqueue the work on `chunks` chunks, one chunk per workgroup, as a sequence
-// of near-equal launches of at most one round of workgroups each.
+// of near-equal launches of at most `rounds_per_launch` rounds of workgroups
+// each.
 // BSGD_LAUNCH_MODE=single (environment, read once) puts everything in one
 // launch instead; kept for comparison.
-int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p) {
+int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p,
+           int rounds_per_launch = 1) {
   if (chunks <= 0) return BSGD_OK;
   if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   static const bool single = [] {
     const char* e = getenv("BSGD_LAUNCH_MODE");
     return e != nullptr && strcmp(e, "single") == 0;
   }();
-  long long round = single ? chunks : round_size(fn, block, lds);
+  long long round = single ? chunks : rounds_per_launch * round_size(fn, block, lds);
   if (2 * chunks < 5 * round) round = chunks;        // small problems are launch-bound: one launch
   const long long launches = (chunks + round - 1) / round;
   const long long per = (chunks + launches - 1) / launches;
@@ -416,7 +419,8 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
-  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p);
+  // the second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails
+  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p, kApplyRoundsPerLaunch);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
