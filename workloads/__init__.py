@@ -9,6 +9,7 @@ from .configs import CONFIGS, StepConfig, get_config, scaled_config  # noqa: F40
 from .gen import (  # noqa: F401
     BLOCK,
     arrival_times,
+    arrival_matrix,
     grad_block,
     grad_row,
     grad_columns,

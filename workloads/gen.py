@@ -22,7 +22,7 @@ from .configs import StepConfig
 
 BLOCK = 1 << 16          # elements per independently seeded block of a row
 
-_S_ARRIVAL, _S_STRAGGLER, _S_WSCALE, _S_TSCALE, _S_TSIZE, _S_THETA, _S_ROW0 = 0, 1, 2, 3, 4, 5, 16
+_S_ARRIVAL, _S_STRAGGLER, _S_WSCALE, _S_TSCALE, _S_TSIZE, _S_THETA, _S_ARRIVAL_MANY, _S_ROW0 = 0, 1, 2, 3, 4, 5, 6, 16
 
 
 def _rng(seed: int, step: int, stream: int, block: int = 0) -> np.random.Generator:
@@ -56,6 +56,25 @@ def arrival_times(cfg: StepConfig, step: int) -> np.ndarray:
             rs = _rng(cfg.seed, step, _S_STRAGGLER)
             slow = rs.random(W) < cfg.straggler_p
             factor = rs.uniform(cfg.straggler_lo, cfg.straggler_hi, W)
+            t = np.where(slow, t * factor, t)
+    else:
+        raise ValueError(cfg.arrival)
+    return t.astype(np.float32)
+
+
+def arrival_matrix(cfg: StepConfig, iterations: int, workers: Optional[int] = None) -> np.ndarray:
+    """fp32[iterations, workers]: arrival times of many recorded iterations at
+    once (the raw material of a straggler analysis), from the configuration's
+    arrival distribution; a stream of its own, drawn in one go."""
+    W = cfg.W if workers is None else int(workers)
+    r = _rng(cfg.seed, 0, _S_ARRIVAL_MANY)
+    if cfg.arrival == "shifted_exp":
+        t = cfg.arrival_shift + r.exponential(1.0 / cfg.arrival_rate, (iterations, W))
+    elif cfg.arrival == "lognormal":
+        t = r.lognormal(0.0, cfg.arrival_sigma, (iterations, W))
+        if cfg.straggler_p > 0.0:
+            slow = r.random((iterations, W)) < cfg.straggler_p
+            factor = r.uniform(cfg.straggler_lo, cfg.straggler_hi, (iterations, W))
             t = np.where(slow, t * factor, t)
     else:
         raise ValueError(cfg.arrival)
