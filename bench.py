@@ -82,6 +82,53 @@ def measured_traffic(plain_c2: bool):
         return None
 
 
+def straggler_main(args, bs, wl) -> int:
+    """Times bsgd_kth_arrival_times (sorted times and their means) on a recording of B iterations of 100 machines
+    with the headline workload's arrival distribution; the oracle is timed beside it on a bounded sample."""
+    import numpy as np
+    import torch
+    from oracle import straggler_oracle as so
+    B, W = args.straggler_iterations, 100
+    a = wl.arrival_matrix(wl.get_config("C2"), B, workers=W)
+    d = torch.from_numpy(a).cuda()
+    kth = torch.empty((B, W), device="cuda")
+    mean = torch.empty(W, device="cuda", dtype=torch.float64)
+    ws = torch.empty(bs.bsgd_straggler_workspace_bytes(W, B), dtype=torch.uint8, device="cuda")
+    for _ in range(args.warmup):
+        bs.bsgd_kth_arrival_times(d, W, B, kth, mean, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        bs.bsgd_kth_arrival_times(d, W, B, kth, mean, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    nb = min(B, 20000)
+    t0 = time.perf_counter()
+    ref = so.mean_kth_time(a[:nb])
+    cpu_s = time.perf_counter() - t0
+    if nb == B:
+        assert np.allclose(mean.cpu().numpy(), ref, rtol=1e-12)
+    io_bytes = 2 * 4 * B * W                      # every time read once and written once
+    slots = 64 * ((W + 63) // 64)
+    cmp_rate = B * slots * W / (ms * 1e-3)
+    cmp_peak = 256 * 64 * 2.4e9 / 2
+    print(json.dumps({
+        "metric": "iterations analysed per second (time to collect k gradients, k = 1..100)", "value": round(B / (ms * 1e-3), 1),
+        "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 keys as u64, f64 sums",
+        "data": "synthetic", "config": {"workload": "straggler analysis", "iterations": B, "machines": W},
+        "roofline": {"bound": "alu", "achieved": round(cmp_rate / 1e12, 3), "peak": round(cmp_peak / 1e12, 3),
+                     "unit": "T key-compares/s", "frac": round(cmp_rate / cmp_peak, 4), "traffic": None,
+                     "note": "each of the 64*ceil(W/64) key slots of an iteration is compared with W keys; a compare "
+                             "of 64-bit keys plus its count is 2 vector instructions; peak = 256 CUs x 64 lanes x "
+                             "2.4 GHz / 2; HBM traffic is only %.0f GB/s" % (io_bytes / (ms * 1e-3) / 1e9)},
+        "cpu_baseline": {"value": round(nb / cpu_s, 1), "unit": "iterations/s", "cores": 1, "kind": "oracle",
+                         "sample": "first %d iterations" % nb}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +143,9 @@ def main() -> int:
     ap.add_argument("--worker-clip", type=float, default=0.0,
                     help="also clip every kept gradient by its own norm (not part of the headline workload)")
     ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal override for the reduce kernel")
+    ap.add_argument("--straggler-iterations", type=int, default=0, metavar="B",
+                    help="time the straggler analysis (time to collect k gradients over B recorded iterations of "
+                         "100 machines) instead of the step; not the headline workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the step shards along P across GPUs by design, "
@@ -113,6 +163,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.tuning:
         bs.bsgd_set_tuning(*[int(x) for x in args.tuning.split(",")])
+
+    if args.straggler_iterations > 0:
+        return straggler_main(args, bs, wl)
 
     cfg = wl.get_config(args.config)
     offs, sizes, P = wl.tensor_layout(cfg)

@@ -228,6 +228,46 @@ int bsgd_last_launch_count(void);
  * makes it the yardstick hardware traffic counters are scaled against. */
 int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Straggler analysis (Sec. 3.1 of the paper, "Straggler effects")
+ * ------------------------------------------------------------------------- */
+
+/* Time to collect k gradients, for B recorded iterations at once.
+ *
+ * arrival_t  DEVICE, fp32 [B x W] row-major: row i holds the arrival times of
+ *            the W workers' gradients in iteration i (+inf or NaN: never
+ *            arrives).  1 <= W <= BSGD_MAX_WORKERS, B >= 1.
+ * kth_time   DEVICE out, fp32 [B x W], or NULL: row i = row i of arrival_t in
+ *            ascending order, so column k-1 is the time at which the
+ *            parameter side held k gradients; never-arriving ones come last
+ *            as +inf.
+ * mean_kth   DEVICE out, fp64 [W], or NULL: mean over the B iterations of
+ *            each column of kth_time (the mean time to collect k gradients),
+ *            accumulated in fp64 in a fixed order (deterministic).
+ * workspace  DEVICE scratch of bsgd_straggler_workspace_bytes(W, B) bytes,
+ *            256-byte aligned; needed only when mean_kth is given.
+ *
+ * Only enqueues on `stream`.  Returns BSGD_OK or BSGD_ERR_ARG / BSGD_ERR_HIP. */
+size_t bsgd_straggler_workspace_bytes(int32_t W, int64_t B);
+int bsgd_kth_arrival_times(const float* arrival_t, int32_t W, int64_t B, float* kth_time, double* mean_kth,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Estimated running time to convergence for every split of W machines into
+ * N kept workers and W-N backups (Sec. 3.1): iterations(N) x mean time to
+ * collect N gradients, where iterations(N) joins the measured points
+ * (measured_N[i], measured_iters[i]) by straight lines and is unknown outside
+ * their range.  HOST arithmetic on HOST arrays, nothing is enqueued.
+ *
+ * mean_kth       HOST, fp64 [W], as written by bsgd_kth_arrival_times.
+ * measured_N/_iters  HOST, fp64 [n_measured], any order, N values distinct.
+ * est            HOST out, fp64 [W]: est[N-1] for N = 1..W, NaN where
+ *                iterations(N) is unknown.
+ * best_N         HOST out: the N with the smallest finite estimate (the larger
+ *                N among equals), 0 if there is none.
+ * Returns BSGD_OK or BSGD_ERR_ARG. */
+int bsgd_time_to_converge(const double* mean_kth, int32_t W, const double* measured_N, const double* measured_iters,
+                          int32_t n_measured, double* est, int32_t* best_N);
+
 /* Human-readable text for a BSGD_* code. */
 const char* bsgd_strerror(int code);
 

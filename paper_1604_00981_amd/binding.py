@@ -97,6 +97,13 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_get_shape.restype = ctypes.c_int
     lib.bsgd_calibration_copy.argtypes = [vp, vp, i64, vp]
     lib.bsgd_calibration_copy.restype = ctypes.c_int
+    lib.bsgd_straggler_workspace_bytes.argtypes = [i32, i64]
+    lib.bsgd_straggler_workspace_bytes.restype = sz
+    lib.bsgd_kth_arrival_times.argtypes = [vp, i32, i64, vp, vp, vp, sz, vp]
+    lib.bsgd_kth_arrival_times.restype = ctypes.c_int
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.bsgd_time_to_converge.argtypes = [dp, i32, dp, dp, i32, dp, ctypes.POINTER(i32)]
+    lib.bsgd_time_to_converge.restype = ctypes.c_int
     lib.bsgd_strerror.argtypes = [ctypes.c_int]
     lib.bsgd_strerror.restype = ctypes.c_char_p
     lib.bsgd_version.argtypes = []
@@ -278,6 +285,37 @@ def bsgd_get_shape(i: int) -> Tuple[int, int, int, int]:
 def bsgd_calibration_copy(dst: DevPtr, src: DevPtr, nbytes: int, stream=None) -> None:
     _check(load_library().bsgd_calibration_copy(_ptr(dst, None, "dst"), _ptr(src, None, "src"), nbytes,
                                                 _stream(stream)), "bsgd_calibration_copy")
+
+
+def bsgd_straggler_workspace_bytes(W: int, B: int) -> int:
+    return int(load_library().bsgd_straggler_workspace_bytes(W, B))
+
+
+def bsgd_kth_arrival_times(arrival_t: DevPtr, W: int, B: int, kth_time: Optional[DevPtr], mean_kth: Optional[DevPtr],
+                           workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Sec. 3.1: per iteration, the time to collect k gradients (rows of
+    arrival_t in ascending order) and/or their mean over iterations."""
+    _check(load_library().bsgd_kth_arrival_times(
+        _ptr(arrival_t, torch.float32, "arrival_t"), W, B,
+        _ptr(kth_time, torch.float32, "kth_time") if kth_time is not None else None,
+        _ptr(mean_kth, torch.float64, "mean_kth") if mean_kth is not None else None,
+        _ptr(workspace, None, "workspace") if workspace is not None else None,
+        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+        _stream(stream)), "bsgd_kth_arrival_times")
+
+
+def bsgd_time_to_converge(mean_kth: Sequence[float], measured: Sequence[Tuple[float, float]]):
+    """Sec. 3.1: (est[W], best_N) from the mean time to collect k gradients
+    and measured (N, iterations) points; host arithmetic inside the library."""
+    W = len(mean_kth)
+    m = (ctypes.c_double * W)(*[float(x) for x in mean_kth])
+    n = len(measured)
+    mn = (ctypes.c_double * max(n, 1))(*[float(p[0]) for p in measured])
+    mi = (ctypes.c_double * max(n, 1))(*[float(p[1]) for p in measured])
+    est = (ctypes.c_double * W)()
+    best = ctypes.c_int32(0)
+    _check(load_library().bsgd_time_to_converge(m, W, mn, mi, n, est, ctypes.byref(best)), "bsgd_time_to_converge")
+    return list(est), int(best.value)
 
 
 def strerror(code: int) -> str:

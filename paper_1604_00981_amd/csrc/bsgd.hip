@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 using namespace bsgd;
@@ -542,6 +543,76 @@ int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* strea
   hipLaunchKernelGGL(k_calibration_copy, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const f4*>(src), static_cast<f4*>(dst), n16);
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
+size_t bsgd_straggler_workspace_bytes(int32_t W, int64_t B) {
+  if (W < 1 || W > BSGD_MAX_WORKERS || B < 1) return 0;
+  const long long slabs = (B + kStragglerSlab - 1) / kStragglerSlab;
+  return round_up(sizeof(double) * (size_t)slabs * (size_t)W, kAlign);
+}
+
+int bsgd_kth_arrival_times(const float* arrival_t, int32_t W, int64_t B, float* kth_time, double* mean_kth,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (arrival_t == nullptr || W < 1 || W > BSGD_MAX_WORKERS || B < 1) return BSGD_ERR_ARG;
+  if (kth_time == nullptr && mean_kth == nullptr) return BSGD_ERR_ARG;
+  const long long slabs = (B + kStragglerSlab - 1) / kStragglerSlab;
+  if (slabs > 0x7fffffffLL) return BSGD_ERR_ARG;
+  double* partial = nullptr;
+  if (mean_kth != nullptr) {
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+        workspace_bytes < bsgd_straggler_workspace_bytes(W, B))
+      return BSGD_ERR_ARG;
+    partial = static_cast<double*>(workspace);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  void (*fn)(const float*, int, long long, float*, double*) =
+      W <= 64 ? k_kth_times<1> : W <= 128 ? k_kth_times<2> : W <= 192 ? k_kth_times<3> : k_kth_times<4>;
+  hipLaunchKernelGGL(fn, dim3((unsigned)slabs), dim3(kStragglerBlock), 0, st, arrival_t, (int)W, (long long)B,
+                     kth_time, partial);
+  if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  if (mean_kth != nullptr) {
+    hipLaunchKernelGGL(k_mean_kth, dim3((unsigned)W), dim3(kMeanBlock), 0, st, (const double*)partial, slabs, (int)W,
+                       (long long)B, mean_kth);
+    if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  }
+  return BSGD_OK;
+}
+
+int bsgd_time_to_converge(const double* mean_kth, int32_t W, const double* measured_N, const double* measured_iters,
+                          int32_t n_measured, double* est, int32_t* best_N) {
+  if (mean_kth == nullptr || est == nullptr || best_N == nullptr || W < 1 || n_measured < 0) return BSGD_ERR_ARG;
+  if (n_measured > 0 && (measured_N == nullptr || measured_iters == nullptr)) return BSGD_ERR_ARG;
+  std::vector<std::pair<double, double>> pts;
+  for (int i = 0; i < n_measured; ++i) {
+    if (measured_N[i] != measured_N[i] || measured_iters[i] != measured_iters[i]) return BSGD_ERR_ARG;
+    pts.emplace_back(measured_N[i], measured_iters[i]);
+  }
+  std::sort(pts.begin(), pts.end());
+  for (size_t i = 1; i < pts.size(); ++i)
+    if (pts[i].first == pts[i - 1].first) return BSGD_ERR_ARG;   // two counts for one N
+  const double nan = std::nan("");
+  *best_N = 0;
+  double best = INFINITY;
+  size_t seg = 0;                                      // pts[seg] <= N <= pts[seg + 1]
+  for (int N = 1; N <= W; ++N) {
+    double iters = nan;
+    if (!pts.empty() && N >= pts.front().first && N <= pts.back().first) {
+      while (seg + 1 < pts.size() && pts[seg + 1].first < N) ++seg;
+      if (pts.size() == 1 || pts[seg].first == N) {
+        iters = pts[seg].second;
+      } else {
+        const double span = pts[seg + 1].first - pts[seg].first;
+        iters = pts[seg].second + (pts[seg + 1].second - pts[seg].second) * ((N - pts[seg].first) / span);
+      }
+    }
+    const double e = iters * mean_kth[N - 1];
+    est[N - 1] = (iters == iters) ? e : nan;
+    if (iters == iters && std::isfinite(e) && e <= best) {
+      best = e;
+      *best_N = N;
+    }
+  }
+  return BSGD_OK;
 }
 
 const char* bsgd_strerror(int code) {

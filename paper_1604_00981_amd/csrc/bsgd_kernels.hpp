@@ -804,6 +804,94 @@ __global__ __launch_bounds__(kFinalizeBlock) void k_finalize_norm(const double* 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Straggler analysis (Sec. 3.1): time to collect k gradients
+// ---------------------------------------------------------------------------
+constexpr int kStragglerBlock = 256;                 // 4 wavefronts; a wavefront takes whole iterations
+constexpr int kStragglerWaves = kStragglerBlock / 64;
+constexpr int kStragglerSlab = 64;                   // iterations per workgroup
+
+// Each wavefront ranks one iteration's W arrival times the way k_select does
+// (distinct 64-bit keys, every key counts the keys below it), writes the
+// times in rank order and adds them, by rank, to its own fp64 sums in LDS.
+// The workgroup's sums go to partial[workgroup][W] in a fixed order.
+// R = slots per lane = ceil(W / 64).
+template <int R>
+__global__ __launch_bounds__(kStragglerBlock) void k_kth_times(const float* __restrict__ arrival_t, int W, long long B,
+                                                                float* __restrict__ kth_time,
+                                                                double* __restrict__ partial) {
+  __shared__ unsigned long long keys[kStragglerWaves][64 * R];
+  __shared__ double acc[kStragglerWaves][64 * R];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[wave][lane + 64 * r] = 0.0;
+  const long long i0 = (long long)blockIdx.x * kStragglerSlab;
+
+  for (int s = wave; s < kStragglerSlab; s += kStragglerWaves) {   // same trip count in every wavefront
+    const long long i = i0 + s;
+    const bool active = i < B;
+    unsigned long long key[R];
+    float tval[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int w = lane + 64 * r;
+      key[r] = ~0ull;                                 // padding: after every real key
+      tval[r] = INFINITY;
+      if (active && w < W) {
+        const float t = arrival_t[i * W + w];
+        const unsigned bits = ordered_time_bits(t);
+        if (bits < kNeverArrives) tval[r] = t;        // else: never arrives, reported as +inf
+        key[r] = ((unsigned long long)bits << 32) | (unsigned)w;
+      }
+      keys[wave][w] = key[r];
+    }
+    __syncthreads();
+    int rank[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rank[r] = 0;
+    if (active) {
+      for (int j = 0; j < W; ++j) {
+        const unsigned long long kj = keys[wave][j];  // LDS broadcast
+#pragma unroll
+        for (int r = 0; r < R; ++r) rank[r] += (kj < key[r]) ? 1 : 0;
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (lane + 64 * r < W) {                      // ranks of real keys are 0..W-1, each taken once
+          if (kth_time != nullptr) kth_time[i * W + rank[r]] = tval[r];
+          acc[wave][rank[r]] += (double)tval[r];
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (partial != nullptr) {
+    for (int r = threadIdx.x; r < W; r += kStragglerBlock) {
+      double sum = acc[0][r];
+#pragma unroll
+      for (int w = 1; w < kStragglerWaves; ++w) sum += acc[w][r];
+      partial[(long long)blockIdx.x * W + r] = sum;
+    }
+  }
+}
+
+// Workgroup k adds column k of partial[slabs][W] in a fixed order and divides by B.
+constexpr int kMeanBlock = 256;
+__global__ __launch_bounds__(kMeanBlock) void k_mean_kth(const double* __restrict__ partial, long long slabs, int W,
+                                                          long long B, double* __restrict__ mean_kth) {
+  __shared__ double red[kMeanBlock];
+  const int k = blockIdx.x;
+  double sum = 0.0;
+  for (long long g = threadIdx.x; g < slabs; g += kMeanBlock) sum += partial[g * W + k];
+  red[threadIdx.x] = sum;
+  __syncthreads();
+  for (int half = kMeanBlock / 2; half > 0; half >>= 1) {
+    if ((int)threadIdx.x < half) red[threadIdx.x] += red[threadIdx.x + half];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) mean_kth[k] = red[0] / (double)B;
+}
+
 // Plain 16-byte-per-thread copy with a known byte count: the yardstick the
 // profiler's HBM read/write counters are scaled against.
 __global__ __launch_bounds__(256) void k_calibration_copy(const f4* __restrict__ src, f4* __restrict__ dst, long long n16) {
