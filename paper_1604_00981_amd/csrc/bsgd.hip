@@ -222,8 +222,11 @@ static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bs
     if (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline) return BSGD_ERR_ARG;
     o = SelectOpts{opts->tags, opts->step_tag, opts->deadline, opts->n_min};
   }
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(64), 0, stream, arrival_t, (int)N, (int)(N + b), o, (int*)sel_idx,
-                     (int*)n_kept, t_step, (int*)status);
+  const int W = N + b;
+  void (*fn)(const float*, int, int, SelectOpts, int*, int*, float*, int*) =
+      W <= 64 ? k_select<1> : W <= 128 ? k_select<2> : W <= 192 ? k_select<3> : k_select<4>;
+  hipLaunchKernelGGL(fn, dim3(1), dim3(64), 0, stream, arrival_t, (int)N, W, o, (int*)sel_idx, (int*)n_kept, t_step,
+                     (int*)status);
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 
