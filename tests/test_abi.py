@@ -153,3 +153,32 @@ def test_tuning_rejects_unknown_shapes():
 def test_build_sources_exist():
     for p in bs_build.SOURCES + bs_build.HEADERS:
         assert os.path.exists(p)
+
+
+def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with a C
+    compiler, and a C program must see the struct layouts the binding uses."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stddef.h>\n#include <stdio.h>\n#include "bsgd.h"\n'
+        "int main(void) {\n"
+        '  printf("hyper %zu", sizeof(bsgd_hyper));\n'
+        + "".join(f'  printf(" %zu", offsetof(bsgd_hyper, {f}));\n' for f, _ in bs.bsgd_hyper._fields_)
+        + '  printf("\\ntensor %zu", sizeof(bsgd_tensor));\n'
+        + "".join(f'  printf(" %zu", offsetof(bsgd_tensor, {f}));\n' for f, _ in bs.bsgd_tensor._fields_)
+        + '  printf("\\nopts %zu", sizeof(bsgd_select_opts));\n'
+        + "".join(f'  printf(" %zu", offsetof(bsgd_select_opts, {f}));\n' for f, _ in bs.bsgd_select_opts._fields_)
+        + '  printf("\\n");\n  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    "-o", str(exe), str(src)], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout.split("\n")
+    for line, st in zip(out, (bs.bsgd_hyper, bs.bsgd_tensor, bs.bsgd_select_opts)):
+        nums = [int(x) for x in line.split()[1:]]
+        assert nums[0] == ctypes.sizeof(st), line
+        assert nums[1:] == [getattr(st, f).offset for f, _ in st._fields_], line
