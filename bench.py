@@ -172,6 +172,8 @@ def main() -> int:
     ap.add_argument("--worker-clip", type=float, default=0.0,
                     help="also clip every kept gradient by its own norm (not part of the headline workload)")
     ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal override for the reduce kernel")
+    ap.add_argument("--ld-pad", type=int, default=0, metavar="ELEMENTS",
+                    help="extra elements between gradient rows (exploration: the headline workload has none)")
     ap.add_argument("--straggler-iterations", type=int, default=0, metavar="B",
                     help="time the straggler analysis (time to collect k gradients over B recorded iterations of "
                          "100 machines) instead of the step; not the headline workload")
@@ -200,7 +202,7 @@ def main() -> int:
     offs, sizes, P = wl.tensor_layout(cfg)
     T, N, b, W = len(sizes), cfg.N, cfg.b, cfg.W
     K, Wm = args.steps, args.warmup
-    ld = (P + 3) // 4 * 4
+    ld = (P + 3) // 4 * 4 + 4 * max(0, args.ld_pad // 4)
     ns = {"sgd": 0, "momentum": 1, "rmsprop_mom": 2}[cfg.opt]
 
     # ---- inputs, resident in HBM before timing -------------------------------------------

@@ -418,3 +418,22 @@ def test_max_workers():
     c = Case(250, 6, [(0, 2051)], "momentum", seed=20)
     c.both(*c.draw())
     c.compare()
+
+
+def test_maximum_number_of_tensors():
+    # 4096 tensors (the documented maximum), tiny and odd-sized, a gap after every third one:
+    # the segment table (tensors and gaps) fills the whole LDS staging area of the multi-tensor path
+    import paper_1604_00981_amd as bs
+    r = np.random.default_rng(77)
+    layout, o = [], 2
+    for j in range(bs.BSGD_MAX_TENSORS):
+        n = int(r.integers(1, 60))
+        layout.append((o, n))
+        o += n + (int(r.integers(1, 9)) if j % 3 == 2 else 0)
+    c = Case(5, 2, layout, "momentum", seed=78, ema=0.9)
+    for _ in range(2):
+        c.both(*c.draw())
+    c.compare()
+    cc = Case(5, 2, layout, "rmsprop_mom", seed=79, hyper=dict(clip_norm=0.05, worker_clip_norm=0.4))
+    cc.both(*cc.draw())
+    cc.compare()
