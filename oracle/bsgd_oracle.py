@@ -21,20 +21,30 @@ What the step is, in the paper's notation:
   * Sec. 1.1 and the last line of Algorithm 4: an exponential moving average
     thetabar of the parameters with decay rate alpha (0.9999 in Appendix A).
 
+  * Sec. 6 (work in progress there): gradients of workers that share a
+    machine are added on that machine before they are sent; the parameter
+    side then receives one message per machine.
+
 Readings where the paper is silent (each is listed in the design notes):
 ties in arrival time go to the lower worker index; an arrival time of +inf
 or NaN means the message never arrives, and fewer than N arrivals means no
 update; momentum is v <- mu v + G, theta <- theta - gamma v; RMSProp with
 momentum is ms <- rho ms + (1-rho) G^2, m <- mu m + gamma G / sqrt(ms + eps),
 theta <- theta - m; clipping acts on the aggregated mean gradient with
-scale min(1, c/||G||).
+scale min(1, c/||G||); a machine's combined message leaves when its last
+worker is done, N then counts messages, and the mean still divides by the
+number of worker gradients the kept messages hold.
 
 Pins (tests/test_oracle_*.py): numpy's stable argsort and an O(W^2)
 definition check for the selection, a message-queue simulation of the
 collect loop, the plain mean for b=0, exact rational arithmetic on tiny
 inputs, NaN-poisoned dropped rows, joint permutation of workers, closed-form
 SGD / momentum / RMSProp trajectories for constant gradients, numpy's norm
-for clipping, closed forms and exact rational replay for the moving average.  No function here is unpinned.
+for clipping, closed forms and exact rational replay for the moving average;
+for pre-combined messages: groups of one are the identity, b=0 equals the
+plain mean over all workers, uniform groups equal the step on the workers
+themselves with their machine's time, exact rational replay.  No function
+here is unpinned.
 """
 from __future__ import annotations
 
@@ -132,6 +142,46 @@ def reduce_mean(grads, sel_idx: Sequence[int], lo: int = 0, hi: Optional[int] = 
     return acc / N
 
 
+def reduce_mean_counted(grads, sel_idx: Sequence[int], row_count: Sequence[int], lo: int = 0,
+                        hi: Optional[int] = None) -> np.ndarray:
+    """Mean over worker gradients when row k already is the sum of
+    row_count[k] of them (Sec. 6): sum of the kept rows / sum of their counts."""
+    total = sum(int(row_count[int(k)]) for k in sel_idx)
+    acc = None
+    for k in sel_idx:
+        row = np.asarray(grads[int(k)][lo:hi], dtype=np.float64)
+        acc = row.copy() if acc is None else acc + row
+    return acc / total
+
+
+def precombine(grads, arrival_t, group_size: Sequence[int]):
+    """Sec. 6: workers that share a machine add their gradients there and
+    the machine sends one message.  Workers of machine m are the next
+    group_size[m] consecutive rows.  The message leaves when the machine's
+    last worker is done (the latest of its workers' times; a worker that
+    never finishes holds its machine back for good).
+
+    Returns (combined fp64 [M, width], arrival fp32 [M], row_count int32 [M])."""
+    t = np.asarray(arrival_t, dtype=np.float32)
+    if sum(int(g) for g in group_size) != t.shape[0] or any(int(g) < 1 for g in group_size):
+        raise ValueError("group sizes must be positive and add up to the number of workers")
+    rows, when, counts = [], [], []
+    k = 0
+    for g in group_size:
+        g = int(g)
+        acc = np.zeros(np.asarray(grads[k]).shape[0], dtype=np.float64)
+        latest = -math.inf
+        for w in range(k, k + g):
+            acc += np.asarray(grads[w], dtype=np.float64)
+            x = float(t[w])
+            latest = max(latest, math.inf if math.isnan(x) else x)
+        rows.append(acc)
+        when.append(latest)
+        counts.append(g)
+        k += g
+    return np.stack(rows), np.array(when, dtype=np.float32), np.array(counts, dtype=np.int32)
+
+
 # ----------------------------------------------------------------------------
 # Appendix A.3: clipping by the global norm over all layers
 # ----------------------------------------------------------------------------
@@ -226,7 +276,10 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
                fp64[numel] (the moving average thetabar, updated in place)
     hyper      dict: opt, lr, momentum, decay, eps, clip_norm, worker_clip_norm,
                ema_decay; and
-               optionally tags, step_tag, deadline, n_min (see select_ex)
+               optionally tags, step_tag, deadline, n_min (see select_ex);
+               optionally row_count int[N+b]: row k is the sum of that many
+               worker gradients (see precombine); not together with
+               worker_clip_norm
 
     Returns (ok, sel_idx, t_step).  ok=False (fewer than N arrivals) leaves
     every tensor untouched.
@@ -242,7 +295,12 @@ def step(grads, arrival_t, N: int, b: int, tensors: List[Dict], hyper: Dict) -> 
 
     ranges = [(int(tz["grad_offset"]), int(tz["grad_offset"]) + tz["theta"].shape[0]) for tz in tensors]
     wc = float(hyper.get("worker_clip_norm", 0.0))
-    if wc > 0.0 and not math.isinf(wc):                 # each worker's own clip comes first
+    counts = hyper.get("row_count")
+    if counts is not None:
+        if wc > 0.0 and not math.isinf(wc):
+            raise ValueError("a combined message cannot be clipped per worker")
+        gbars = [reduce_mean_counted(grads, sel_idx, counts, lo, hi) for lo, hi in ranges]
+    elif wc > 0.0 and not math.isinf(wc):               # each worker's own clip comes first
         scales = worker_clip_scales(grads, sel_idx, ranges, wc)
         gbars = [reduce_mean_scaled(grads, sel_idx, scales, lo, hi) for lo, hi in ranges]
     else:
