@@ -111,6 +111,46 @@ def measured_traffic(plain_c2: bool):
         return None
 
 
+def precombine_main(args, bs, wl) -> int:
+    """Times bsgd_precombine on the workload's gradient matrix, machines of G consecutive workers."""
+    import numpy as np
+    import torch
+    cfg = wl.get_config(args.config)
+    _, _, P = wl.tensor_layout(cfg)
+    W, G = cfg.W, args.precombine
+    sizes = [G] * (W // G) + ([W % G] if W % G else [])
+    M = len(sizes)
+    ld = (P + 3) // 4 * 4
+    g_pin = torch.zeros((W, ld), dtype=torch.float32, pin_memory=True)
+    wl.grad_matrix(cfg, 0, out=g_pin.numpy(), ld=ld)
+    grads = g_pin.cuda()
+    del g_pin
+    t = torch.from_numpy(wl.arrival_times(cfg, 0)).cuda()
+    comb = torch.empty((M, ld), device="cuda")
+    when = torch.empty(M, device="cuda")
+    cnt = torch.empty(M, dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        bs.bsgd_precombine(grads, ld, P, t, sizes, comb, ld, when, cnt)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        bs.bsgd_precombine(grads, ld, P, t, sizes, comb, ld, when, cnt)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    nbytes = (W + M) * P * 4
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "pre-combine GB/s (rows read once, machine sums written once)", "value": round(gbs, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {W} workers on {M} machines of {G}, P={P}"},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}}))
+    return 0
+
+
 def straggler_main(args, bs, wl) -> int:
     """Times bsgd_kth_arrival_times (sorted times and their means) on a recording of B iterations of 100 machines
     with the headline workload's arrival distribution; the oracle is timed beside it on a bounded sample."""
@@ -174,6 +214,9 @@ def main() -> int:
     ap.add_argument("--tuning", default="", help="block,vec,unroll,nontemporal override for the reduce kernel")
     ap.add_argument("--ld-pad", type=int, default=0, metavar="ELEMENTS",
                     help="extra elements between gradient rows (exploration: the headline workload has none)")
+    ap.add_argument("--precombine", type=int, default=0, metavar="G",
+                    help="time bsgd_precombine (one message per machine of G workers) on the workload's gradient "
+                         "matrix instead of the step; not the headline workload")
     ap.add_argument("--straggler-iterations", type=int, default=0, metavar="B",
                     help="time the straggler analysis (time to collect k gradients over B recorded iterations of "
                          "100 machines) instead of the step; not the headline workload")
@@ -197,6 +240,9 @@ def main() -> int:
 
     if args.straggler_iterations > 0:
         return straggler_main(args, bs, wl)
+
+    if args.precombine > 0:
+        return precombine_main(args, bs, wl)
 
     cfg = wl.get_config(args.config)
     offs, sizes, P = wl.tensor_layout(cfg)

@@ -125,6 +125,15 @@ typedef struct {
                            = BSGD_ERR_TOO_FEW).  >= 1: keep EVERY eligible message,
                            any number from n_min to N+b (fewer than n_min =
                            BSGD_ERR_TOO_FEW); the mean then divides by the number kept */
+  const int32_t* row_count; /* DEVICE int32[N+b] or NULL: row k already is the sum of
+                           row_count[k] >= 1 worker gradients, added on the machine
+                           those workers share before it was sent (Sec. 6; see
+                           bsgd_precombine).  N, b and n_min keep counting messages
+                           (rows); the mean divides by the number of worker gradients
+                           the kept rows hold.  Only bsgd_step_ex takes it
+                           (bsgd_select_ex refuses it), and not together with
+                           worker_clip_norm.  A kept row with a count < 1 sets the
+                           status word to BSGD_ERR_ARG and nothing is updated.      */
 } bsgd_select_opts;
 
 /* As bsgd_select_first_n, under `opts`.
@@ -191,6 +200,11 @@ int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, f
  * bsgd_step_ex on this workspace kept (HOST out). */
 int bsgd_last_kept_count(const void* workspace, void* stream, int32_t* n_kept_out);
 
+/* Synchronises `stream`, then reports how many worker gradients the rows kept
+ * by the last bsgd_step / bsgd_step_ex on this workspace hold: the divisor of
+ * the mean (equal to the kept count unless row_count was given).  HOST out. */
+int bsgd_last_gradient_count(const void* workspace, void* stream, int32_t* n_gradients_out);
+
 /* Synchronises `stream`, then copies the N kept worker indices of the last
  * bsgd_step on this workspace to HOST int32[N]. */
 int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t* sel_idx_out);
@@ -227,6 +241,28 @@ int bsgd_last_launch_count(void);
  * not overlapping).  It reads and writes exactly `bytes` bytes of HBM, which
  * makes it the yardstick hardware traffic counters are scaled against. */
 int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
+/* Sec. 6 of the paper: gradients of workers that share a machine are added
+ * on that machine before they are sent, so the parameter side receives one
+ * message per machine.  This is that addition, for M machines at once;
+ * machine m's workers are the next group_size[m] consecutive rows of `grads`.
+ *
+ *   grads       DEVICE fp32 [W x ld], W = sum of group_size; 16-byte aligned,
+ *               ld a multiple of 4 and >= cols.
+ *   cols        columns to combine (the gradient length).
+ *   arrival_t   DEVICE fp32 [W]: when each worker finished (+inf/NaN: never).
+ *   group_size  HOST int32 [M], every entry >= 1, 1 <= M <= W <= BSGD_MAX_WORKERS.
+ *   combined    DEVICE out fp32 [M x ld_out]: row m = sum of machine m's rows,
+ *               added in ascending worker index in fp32; same alignment rules;
+ *               must not overlap grads.
+ *   arrival_m   DEVICE out fp32 [M]: when machine m's message leaves: the
+ *               latest of its workers' times (+inf if one never finishes).
+ *   row_count   DEVICE out int32 [M]: group_size, for bsgd_select_opts.row_count.
+ *
+ * Only enqueues on `stream`; allocates nothing.  BSGD_OK, BSGD_ERR_ARG or BSGD_ERR_HIP. */
+int bsgd_precombine(const float* grads, int64_t ld, int64_t cols, const float* arrival_t,
+                    const int32_t* group_size, int32_t M,
+                    float* combined, int64_t ld_out, float* arrival_m, int32_t* row_count, void* stream);
 
 /* ---------------------------------------------------------------------------
  * Straggler analysis (Sec. 3.1 of the paper, "Straggler effects")

@@ -40,7 +40,7 @@ class bsgd_tensor(ctypes.Structure):
 
 class bsgd_select_opts(ctypes.Structure):
     _fields_ = [("tags", ctypes.c_void_p), ("step_tag", ctypes.c_int32), ("deadline", ctypes.c_float),
-                ("n_min", ctypes.c_int32)]
+                ("n_min", ctypes.c_int32), ("row_count", ctypes.c_void_p)]
 
 
 class BsgdError(RuntimeError):
@@ -97,6 +97,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_get_shape.restype = ctypes.c_int
     lib.bsgd_calibration_copy.argtypes = [vp, vp, i64, vp]
     lib.bsgd_calibration_copy.restype = ctypes.c_int
+    lib.bsgd_last_gradient_count.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.bsgd_last_gradient_count.restype = ctypes.c_int
+    lib.bsgd_precombine.argtypes = [vp, i64, i64, vp, ctypes.POINTER(i32), i32, vp, i64, vp, vp, vp]
+    lib.bsgd_precombine.restype = ctypes.c_int
     lib.bsgd_straggler_workspace_bytes.argtypes = [i32, i64]
     lib.bsgd_straggler_workspace_bytes.restype = sz
     lib.bsgd_kth_arrival_times.argtypes = [vp, i32, i64, vp, vp, vp, sz, vp]
@@ -164,9 +168,11 @@ def make_tensors(items: Iterable[Tuple[DevPtr, DevPtr, DevPtr, int, int]]):
     return arr
 
 
-def make_select_opts(tags: DevPtr = None, step_tag: int = 0, deadline: float = float("inf"), n_min: int = 0):
-    """bsgd_select_opts; keep the tags tensor alive as long as the struct is used."""
-    return bsgd_select_opts(_ptr(tags, torch.int32, "tags"), step_tag, deadline, n_min)
+def make_select_opts(tags: DevPtr = None, step_tag: int = 0, deadline: float = float("inf"), n_min: int = 0,
+                     row_count: DevPtr = None):
+    """bsgd_select_opts; keep the tags / row_count tensors alive as long as the struct is used."""
+    return bsgd_select_opts(_ptr(tags, torch.int32, "tags"), step_tag, deadline, n_min,
+                            _ptr(row_count, torch.int32, "row_count"))
 
 
 def _check(rc: int, where: str) -> None:
@@ -285,6 +291,24 @@ def bsgd_get_shape(i: int) -> Tuple[int, int, int, int]:
 def bsgd_calibration_copy(dst: DevPtr, src: DevPtr, nbytes: int, stream=None) -> None:
     _check(load_library().bsgd_calibration_copy(_ptr(dst, None, "dst"), _ptr(src, None, "src"), nbytes,
                                                 _stream(stream)), "bsgd_calibration_copy")
+
+
+def bsgd_last_gradient_count(workspace: torch.Tensor, stream=None) -> int:
+    out = ctypes.c_int32(0)
+    _check(load_library().bsgd_last_gradient_count(_ptr(workspace, None, "workspace"), _stream(stream),
+                                                   ctypes.byref(out)), "bsgd_last_gradient_count")
+    return int(out.value)
+
+
+def bsgd_precombine(grads: DevPtr, ld: int, cols: int, arrival_t: DevPtr, group_size: Sequence[int],
+                    combined: DevPtr, ld_out: int, arrival_m: DevPtr, row_count: DevPtr, stream=None) -> None:
+    """Sec. 6: one message per machine = the sum of its workers' gradient rows."""
+    M = len(group_size)
+    gs = (ctypes.c_int32 * max(M, 1))(*[int(g) for g in group_size])
+    _check(load_library().bsgd_precombine(
+        _ptr(grads, torch.float32, "grads"), ld, cols, _ptr(arrival_t, torch.float32, "arrival_t"), gs, M,
+        _ptr(combined, torch.float32, "combined"), ld_out, _ptr(arrival_m, torch.float32, "arrival_m"),
+        _ptr(row_count, torch.int32, "row_count"), _stream(stream)), "bsgd_precombine")
 
 
 def bsgd_straggler_workspace_bytes(W: int, B: int) -> int:

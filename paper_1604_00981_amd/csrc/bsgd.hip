@@ -216,11 +216,12 @@ bool check_select_args(const float* arrival_t, int N, int b) {
 extern "C" {
 
 static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts,
-                          int32_t* sel_idx, int32_t* n_kept, float* t_step, int32_t* status, hipStream_t stream) {
-  SelectOpts o{nullptr, 0, INFINITY, 0};
+                          int32_t* sel_idx, int32_t* n_kept, int32_t* n_grad, float* t_step, int32_t* status,
+                          hipStream_t stream) {
+  SelectOpts o{nullptr, 0, INFINITY, 0, nullptr, (int*)n_grad};
   if (opts != nullptr) {
     if (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline) return BSGD_ERR_ARG;
-    o = SelectOpts{opts->tags, opts->step_tag, opts->deadline, opts->n_min};
+    o = SelectOpts{opts->tags, opts->step_tag, opts->deadline, opts->n_min, opts->row_count, (int*)n_grad};
   }
   const int W = N + b;
   void (*fn)(const float*, int, int, SelectOpts, int*, int*, float*, int*) =
@@ -233,7 +234,7 @@ static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bs
 int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b, int32_t* sel_idx, float* t_step,
                         int32_t* status, void* stream) {
   if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr) return BSGD_ERR_ARG;
-  return enqueue_select(arrival_t, N, b, nullptr, sel_idx, nullptr, t_step, status, (hipStream_t)stream);
+  return enqueue_select(arrival_t, N, b, nullptr, sel_idx, nullptr, nullptr, t_step, status, (hipStream_t)stream);
 }
 
 int bsgd_select_ex(const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts, int32_t* sel_idx,
@@ -241,7 +242,8 @@ int bsgd_select_ex(const float* arrival_t, int32_t N, int32_t b, const bsgd_sele
   if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr || opts == nullptr)
     return BSGD_ERR_ARG;
   if (opts->n_min > 0 && n_kept == nullptr) return BSGD_ERR_ARG;   // the count is the only way to know how many
-  return enqueue_select(arrival_t, N, b, opts, sel_idx, n_kept, t_step, status, (hipStream_t)stream);
+  if (opts->row_count != nullptr) return BSGD_ERR_ARG;             // the divisor lives in a step's workspace
+  return enqueue_select(arrival_t, N, b, opts, sel_idx, n_kept, nullptr, t_step, status, (hipStream_t)stream);
 }
 
 size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const bsgd_hyper* hyper) {
@@ -339,7 +341,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
 }
 
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
-                          const int32_t* n_dev, int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan,
+                          const int32_t* n_dev, const int32_t* div_dev, int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan,
                           hipStream_t stream) {
   t_last_launches = 0;
   if (plan.S == 0) return BSGD_OK;
@@ -357,6 +359,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.N = N;
   p.inv_n = 1.0f / (float)N;
   p.n_dev = n_dev;
+  p.div_dev = div_dev;
   p.row_scale = wclip ? reinterpret_cast<const float*>(ws + L.rowscale_off) : nullptr;
   p.row_partials = reinterpret_cast<double*>(ws + L.rowpart_off);
   p.n_stride = N;
@@ -434,7 +437,8 @@ int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, c
   Plan plan;
   int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel_idx, status, N, nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
+  return enqueue_update(grads, ld, sel_idx, status, N, nullptr, nullptr, T, hyper, workspace, plan,
+                        (hipStream_t)stream);
 }
 
 static int step_common(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
@@ -442,6 +446,8 @@ static int step_common(const float* grads, int64_t ld, const float* arrival_t, i
                        void* workspace, size_t workspace_bytes, void* stream) {
   if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
   if (opts != nullptr && (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline)) return BSGD_ERR_ARG;
+  const bool counted = opts != nullptr && opts->row_count != nullptr;
+  if (counted && hyper != nullptr && worker_clip_on(hyper)) return BSGD_ERR_ARG;   // a sum of gradients has no single worker's norm
   Plan plan;
   // in deadline mode up to N+b rows may be kept
   const bool all_in_time = opts != nullptr && opts->n_min > 0;
@@ -450,10 +456,11 @@ static int step_common(const float* grads, int64_t ld, const float* arrival_t, i
   char* ws = static_cast<char*>(workspace);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
   int* sel = reinterpret_cast<int*>(ws + kAlign);
-  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->t_step, &hdr->status, (hipStream_t)stream);
+  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->n_grad, &hdr->t_step, &hdr->status,
+                      (hipStream_t)stream);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? &hdr->n_kept : nullptr, T, hyper, workspace,
-                        plan, (hipStream_t)stream);
+  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? &hdr->n_kept : nullptr,
+                        counted ? &hdr->n_grad : nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
 }
 
 int bsgd_step(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
@@ -485,6 +492,15 @@ int bsgd_last_kept_count(const void* workspace, void* stream, int32_t* n_kept_ou
   WsHeader h;
   if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
   *n_kept_out = h.n_kept;
+  return BSGD_OK;
+}
+
+int bsgd_last_gradient_count(const void* workspace, void* stream, int32_t* n_gradients_out) {
+  if (workspace == nullptr || n_gradients_out == nullptr) return BSGD_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BSGD_ERR_HIP;
+  WsHeader h;
+  if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return BSGD_ERR_HIP;
+  *n_gradients_out = h.n_grad;
   return BSGD_OK;
 }
 
@@ -545,6 +561,44 @@ int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* strea
   if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
   hipLaunchKernelGGL(k_calibration_copy, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const f4*>(src), static_cast<f4*>(dst), n16);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
+int bsgd_precombine(const float* grads, int64_t ld, int64_t cols, const float* arrival_t, const int32_t* group_size,
+                    int32_t M, float* combined, int64_t ld_out, float* arrival_m, int32_t* row_count, void* stream) {
+  if (grads == nullptr || arrival_t == nullptr || group_size == nullptr || combined == nullptr ||
+      arrival_m == nullptr || row_count == nullptr)
+    return BSGD_ERR_ARG;
+  if (M < 1 || M > BSGD_MAX_WORKERS || cols < 1 || ld < cols || ld_out < cols || (ld & 3) != 0 || (ld_out & 3) != 0)
+    return BSGD_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(grads) & 15) != 0 || (reinterpret_cast<uintptr_t>(combined) & 15) != 0)
+    return BSGD_ERR_ARG;
+  CombineParams p{};
+  long long W = 0;
+  for (int m = 0; m < M; ++m) {
+    if (group_size[m] < 1 || W + group_size[m] > BSGD_MAX_WORKERS) return BSGD_ERR_ARG;
+    p.first[m] = (unsigned char)W;
+    W += group_size[m];
+  }
+  p.last = (int)W;
+  // the output may not overlap the input
+  const uintptr_t g0 = reinterpret_cast<uintptr_t>(grads), g1 = g0 + sizeof(float) * (size_t)W * (size_t)ld;
+  const uintptr_t c0 = reinterpret_cast<uintptr_t>(combined), c1 = c0 + sizeof(float) * (size_t)M * (size_t)ld_out;
+  if (c0 < g1 && g0 < c1) return BSGD_ERR_ARG;
+  p.grads = grads;
+  p.ld = ld;
+  p.combined = combined;
+  p.ld_out = ld_out;
+  p.cols4 = (cols + 3) & ~3LL;
+  p.M = M;
+  using S = Shape<256, 8, 2, true>;
+  const long long chunk_cols = 4LL * S::BS * S::V;
+  const long long chunks = (p.cols4 + chunk_cols - 1) / chunk_cols;
+  if (chunks > 0x7fffffffLL) return BSGD_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(k_precombine<S>, dim3((unsigned)chunks, (unsigned)M), dim3(S::BS), 0, st, p);
+  if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  hipLaunchKernelGGL(k_machine_arrival, dim3(1), dim3(64), 0, st, arrival_t, p, arrival_m, (int*)row_count);
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 

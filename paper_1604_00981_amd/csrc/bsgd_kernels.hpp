@@ -58,8 +58,9 @@ struct WsHeader {
   int status;          // BSGD_OK or BSGD_ERR_TOO_FEW
   float t_step;        // arrival time of the N-th kept gradient
   float clip_scale;    // min(1, c/||G||)
-  int n_kept;          // how many gradients the step kept
+  int n_kept;          // how many rows (messages) the step kept
   double norm;         // ||G|| before clipping
+  int n_grad;          // how many worker gradients those rows hold: the divisor of the mean
 };
 
 struct StepParams {
@@ -70,6 +71,7 @@ struct StepParams {
   int N;
   float inv_n;
   const int* n_dev;          // when set: the number of kept rows is read from here (deadline mode)
+  const int* div_dev;        // when set: the divisor of the mean is read from here (rows that hold several gradients)
   const float* row_scale;    // per kept row: its own clip scale (per-worker clipping), or null
   double* row_partials;      // [chunk][n_stride]: per chunk and kept row, sum of squares (per-worker clipping)
   int n_stride;              // rows per chunk in row_partials
@@ -111,6 +113,8 @@ struct SelectOpts {
   int step_tag;        // messages with another tag are dropped (Algorithm 4's tag test)
   float deadline;      // messages arriving later are dropped; +inf: none
   int n_min;           // 0: keep the first N eligible; >= 1: keep every eligible one, at least n_min
+  const int* row_count;  // worker gradients each row holds, or null (one each)
+  int* n_grad;           // out: worker gradients held by the kept rows, or null
 };
 
 // One wavefront.  Worker w = lane + 64*r sits in slot r of its lane; its key
@@ -174,9 +178,26 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
     base += __popcll(mask);
     if ((w < W) && rank[r] == K - 1 && t_step) *t_step = tval[r];   // the last kept arrival: how long the step waited
   }
+  // rows that already combine several workers' gradients: the mean divides by the gradients kept
+  int held = 0, bad = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int w = lane + 64 * r;
+    if ((w < W) && (rank[r] < K) && !too_few) {
+      const int c = o.row_count != nullptr ? o.row_count[w] : 1;
+      held += c;
+      bad |= (c < 1) ? 1 : 0;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    held += __shfl_xor(held, off, 64);
+    bad |= __shfl_xor(bad, off, 64);
+  }
   if (lane == 0) {
-    *status = too_few ? -2 : 0;
+    *status = too_few ? -2 : (bad ? -1 : 0);
     if (n_kept) *n_kept = too_few ? 0 : K;
+    if (o.n_grad) *o.n_grad = held;
   }
 }
 
@@ -426,7 +447,8 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
 
   if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
   const int n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
-  const float inv_n = p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n;
+  const float inv_n = p.div_dev != nullptr ? 1.0f / (float)*p.div_dev
+                                           : (p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n);
 
   if constexpr (MULTI) {
     for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
@@ -806,6 +828,82 @@ __global__ __launch_bounds__(kFinalizeBlock) void k_finalize_norm(const double* 
     const double nrm = sqrt(red[0]);
     header->norm = nrm;
     header->clip_scale = (nrm <= (double)c) ? 1.0f : (float)((double)c / nrm);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Sec. 6: one message per machine (sum of the gradients of its workers)
+// ---------------------------------------------------------------------------
+struct CombineParams {
+  const float* grads;        // [W x ld]
+  long long ld;
+  float* combined;           // [M x ld_out]
+  long long ld_out;
+  long long cols4;           // gradient length rounded up to a multiple of 4
+  int M;
+  unsigned char first[kMaxWorkers + 1];   // first row of each machine, then W (W <= 256 needs 9 bits: see last)
+  int last;                  // W
+};
+
+// Workgroup (chunk, machine): adds the machine's rows over one chunk of
+// columns, same chunking, row order and load shape as k_step's row loop.
+template <class S>
+__global__ __launch_bounds__(S::BS) void k_precombine(CombineParams p) {
+  constexpr int BS = S::BS, V = S::V, U = S::U;
+  constexpr bool NT = S::NT;
+  constexpr long long CH = 4LL * BS * V;
+  const int m = blockIdx.y;
+  const long long c0 = (long long)blockIdx.x * CH;
+  const int r0 = p.first[m];
+  const int r1 = (m + 1 == p.M) ? p.last : (int)p.first[m + 1];
+  unsigned toff[V];
+  bool valid[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    const int g = S::group_of(v);
+    valid[v] = c0 + 4LL * g < p.cols4;
+    toff[v] = valid[v] ? (unsigned)g * 16u : 0u;
+  }
+  f4 acc[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) acc[v] = f4{0.f, 0.f, 0.f, 0.f};
+  for (int j = r0; j < r1; j += U) {
+    f4 r[U][V];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = j + u < r1 ? j + u : r1 - 1;
+      const char* rowbase = reinterpret_cast<const char*>(p.grads + (long long)row * p.ld + c0);
+#pragma unroll
+      for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (j + u < r1) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += r[u][v];
+      }
+    }
+  }
+  float* out = p.combined + (long long)m * p.ld_out + c0;
+#pragma unroll
+  for (int v = 0; v < V; ++v)
+    if (valid[v]) store_state<NT>(acc[v], reinterpret_cast<uintptr_t>(out) + toff[v]);
+}
+
+// One wavefront: machine m's message leaves with its last worker.
+__global__ __launch_bounds__(64) void k_machine_arrival(const float* __restrict__ arrival_t, CombineParams p,
+                                                         float* __restrict__ arrival_m, int* __restrict__ row_count) {
+  for (int m = threadIdx.x; m < p.M; m += 64) {
+    const int r0 = p.first[m];
+    const int r1 = (m + 1 == p.M) ? p.last : (int)p.first[m + 1];
+    float latest = -INFINITY;
+    for (int w = r0; w < r1; ++w) {
+      const float t = arrival_t[w];
+      latest = (t != t) ? INFINITY : (t > latest ? t : latest);   // NaN: never finishes
+      if (latest == INFINITY) break;
+    }
+    arrival_m[m] = latest;
+    row_count[m] = r1 - r0;
   }
 }
 
