@@ -1,15 +1,19 @@
 // Device code for the backup-worker Sync-SGD step on gfx950 (CDNA4).
 //
-// Three pieces, all bandwidth- or latency-bound (no dense contraction, so no
-// MFMA):
+// All of it is bandwidth- or latency-bound (no dense contraction, so no MFMA):
 //   k_select         one wavefront ranks the N+b arrival times and writes the
-//                    kept set (Algorithm 4, collect loop).
-//   k_reduce_update  one streaming pass: gather-sum of the N kept gradient
-//                    rows in registers, mean, fused optimizer update
-//                    (Algorithm 4, update line; Sec. 3 "Sync-Opt").
-//   k_finalize_norm / k_apply   the second half of a clipped step (global-norm
-//                    clipping as in Appendix A.3): reduce the per-block sums
-//                    of squares, then scale the stored mean and update.
+//                    kept set (Algorithm 4, collect loop; tags and the
+//                    time-out variant of Sec. 6 as options).
+//   k_step           one streaming pass: gather-sum of the kept gradient rows
+//                    in registers, mean, fused optimizer update and moving
+//                    average (Algorithm 4, update lines; Sec. 3 "Sync-Opt").
+//                    The same kernel, instantiated differently, is both
+//                    halves of a step clipped by the global norm (Appendix
+//                    A.3): rows -> stored mean + sums of squares, then stored
+//                    mean x scale -> update; k_finalize_norm sits in between.
+//   k_row_sumsq / k_row_scales   per-worker clipping (Appendix A.3 as printed).
+//   k_precombine / k_machine_arrival   one message per machine (Sec. 6).
+//   k_kth_times / k_mean_kth     time to collect k gradients (Sec. 3.1).
 #pragma once
 
 
