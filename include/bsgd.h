@@ -231,6 +231,14 @@ int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontempo
 int bsgd_num_shapes(void);
 int bsgd_get_shape(int32_t i, int32_t* out4);
 
+/* How a multi-tensor call hands its tensor table to the kernels, process-wide;
+ * for testing and benchmarking.  mode 0 (default): every launch carries the
+ * part of the table its columns fall into as a kernel argument, and only a
+ * call in which some launch touches more tensors than fit there writes the
+ * whole table into the workspace first; mode 1: always through the workspace.
+ * Results do not depend on it.  Returns BSGD_ERR_ARG for another mode. */
+int bsgd_set_table_mode(int32_t mode);
+
 /* How many launches of the reduce/update kernel the calling thread's last
  * bsgd_step / bsgd_reduce_update enqueued (a step is cut into launches that
  * each fill the chip once; a clipped step counts both of its passes). */

@@ -89,6 +89,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_last_clip.restype = ctypes.c_int
     lib.bsgd_set_tuning.argtypes = [i32, i32, i32, i32]
     lib.bsgd_set_tuning.restype = ctypes.c_int
+    lib.bsgd_set_table_mode.argtypes = [i32]
+    lib.bsgd_set_table_mode.restype = ctypes.c_int
     lib.bsgd_last_launch_count.argtypes = []
     lib.bsgd_last_launch_count.restype = ctypes.c_int
     lib.bsgd_num_shapes.argtypes = []
@@ -268,6 +270,11 @@ def bsgd_last_clip(workspace: DevPtr, stream=None) -> Tuple[float, float]:
     _check(load_library().bsgd_last_clip(_ptr(workspace, None, "workspace"), _stream(stream),
                                          ctypes.byref(nrm), ctypes.byref(sc)), "bsgd_last_clip")
     return nrm.value, sc.value
+
+
+def bsgd_set_table_mode(mode: int = 0) -> None:
+    """0: launches carry their part of the tensor table as an argument when it fits; 1: always via the workspace."""
+    _check(load_library().bsgd_set_table_mode(mode), "bsgd_set_table_mode")
 
 
 def bsgd_set_tuning(block: int = -1, vec: int = -1, unroll: int = -1, nontemporal: int = -1) -> None:

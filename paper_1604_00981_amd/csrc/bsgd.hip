@@ -41,7 +41,7 @@ bool worker_clip_on(const bsgd_hyper* h) {
 // ---------------------------------------------------------------------------
 // kernel variants (launch shapes)
 // ---------------------------------------------------------------------------
-using StepKernel = void (*)(StepParams);
+using StepKernel = const void*;                      // k_step / k_row_sumsq instantiations: (StepParams, TableArg<multi>)
 
 struct Variant {
   int BS, V, U, NT;
@@ -51,25 +51,17 @@ struct Variant {
   StepKernel apply[3][2][2]; // [mode][multi][ema]   clipped step, pass 2: gradient from the stored mean
 };
 
-template <int MODE, class SH, bool ROWS>
-struct KernelsOf {                                   // [multi][ema]
-  static constexpr StepKernel single_plain = k_step<MODE, SH, false, ROWS, false>;
-  static constexpr StepKernel single_ema = k_step<MODE, SH, false, ROWS, true>;
-  static constexpr StepKernel multi_plain = k_step<MODE, SH, true, ROWS, false>;
-  static constexpr StepKernel multi_ema = k_step<MODE, SH, true, ROWS, true>;
-};
-
 template <int BS, int V, int U, int NT>
 Variant make_variant() {
   using R = Shape<BS, V, U, NT != 0>;                // row loop shape
   using A = Shape<BS, V, 1, NT != 0>;                // pass 2 of a clipped step reads one stored row
   Variant v{};
   v.BS = BS; v.V = V; v.U = U; v.NT = NT;
-#define BSGD_FILL(dst, MODE, SH, ROWS)                                   \
-  dst[0][0] = KernelsOf<MODE, SH, ROWS>::single_plain;                   \
-  dst[0][1] = KernelsOf<MODE, SH, ROWS>::single_ema;                     \
-  dst[1][0] = KernelsOf<MODE, SH, ROWS>::multi_plain;                    \
-  dst[1][1] = KernelsOf<MODE, SH, ROWS>::multi_ema;
+#define BSGD_FILL(dst, MODE, SH, ROWS)                                                      \
+  dst[0][0] = reinterpret_cast<StepKernel>(&k_step<MODE, SH, false, ROWS, false>);          \
+  dst[0][1] = reinterpret_cast<StepKernel>(&k_step<MODE, SH, false, ROWS, true>);           \
+  dst[1][0] = reinterpret_cast<StepKernel>(&k_step<MODE, SH, true, ROWS, false>);           \
+  dst[1][1] = reinterpret_cast<StepKernel>(&k_step<MODE, SH, true, ROWS, true>);
   BSGD_FILL(v.rows[kSgd], kSgd, R, true)
   BSGD_FILL(v.rows[kMomentum], kMomentum, R, true)
   BSGD_FILL(v.rows[kRmspropMom], kRmspropMom, R, true)
@@ -77,10 +69,10 @@ Variant make_variant() {
   BSGD_FILL(v.apply[kMomentum], kMomentum, A, false)
   BSGD_FILL(v.apply[kRmspropMom], kRmspropMom, A, false)
 #undef BSGD_FILL
-  v.reduce[0] = k_step<kClipReduce, R, false, true, false>;
-  v.reduce[1] = k_step<kClipReduce, R, true, true, false>;
-  v.rowsq[0] = k_row_sumsq<R, false>;
-  v.rowsq[1] = k_row_sumsq<R, true>;
+  v.reduce[0] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, false, true, false>);
+  v.reduce[1] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, true, true, false>);
+  v.rowsq[0] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, false>);
+  v.rowsq[1] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, true>);
   return v;
 }
 #define BSGD_VARIANT(BS, V, U, NT) make_variant<BS, V, U, NT>()
@@ -170,7 +162,7 @@ long long round_size(StepKernel fn, int block, size_t lds) {
   for (const Entry& e : cache)
     if (e.fn == fn && e.lds == lds) return e.n;
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), block, lds) != hipSuccess || per_cu < 1)
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, block, lds) != hipSuccess || per_cu < 1)
     per_cu = 1;
   const int cap = (8 * 64) / block > 0 ? (8 * 64) / block : 1;
   if (per_cu > cap) per_cu = cap;
@@ -179,29 +171,144 @@ long long round_size(StepKernel fn, int block, size_t lds) {
   return n;
 }
 
-// Enqueue the work on `chunks` chunks, one chunk per workgroup, as a sequence
-// of near-equal launches of at most `rounds_per_launch` rounds of workgroups
-// each.
+// What a call will run on: the tensors as sorted, non-overlapping segments of
+// the gradient row (gaps made explicit), built and checked on the host.
+struct Plan {
+  long long span = 0;                 // largest grad_offset + numel
+  long long col_lo = 0, col_hi = 0;   // columns covered: [col_lo, col_hi)
+  int S = 0;                          // segments (S == 1: `single` is used, the vectors stay empty)
+  Segment single{};
+  bool ema = false;                   // every tensor carries a moving average
+  std::vector<Segment> segs;
+  std::vector<unsigned> starts;       // S + 1 entries
+};
+
+
+// The segment table of a multi-tensor call during one enqueue_update: where
+// the workspace copy lives and whether this call has written it yet.
+struct TableCtx {
+  const Plan* plan;
+  Segment* d_table;
+  unsigned* d_starts;
+  bool uploaded;
+};
+
+// kernel arguments are limited to 4 KiB: StepParams and the embedded table must fit together
+static_assert((sizeof(StepParams) + alignof(EmbeddedTable) - 1) / alignof(EmbeddedTable) * alignof(EmbeddedTable) +
+                      sizeof(EmbeddedTable) <= 4096,
+              "StepParams + EmbeddedTable exceed the kernel-argument buffer");
+std::atomic<int> g_table_mode{0};                    // 0: by size; 1: always through the workspace
+
+// Writes the whole table into the workspace (kernel launches that carry the
+// descriptors as arguments; no host-to-device copy).
+int upload_table(TableCtx& tc, hipStream_t stream) {
+  const Plan& plan = *tc.plan;
+  for (int first = 0; first < plan.S; first += kUploadBatch) {
+    UploadArgs a{};
+    a.first = first;
+    a.count = (plan.S - first < kUploadBatch) ? (plan.S - first) : kUploadBatch;
+    for (int i = 0; i < a.count; ++i) {
+      a.seg[i] = plan.segs[first + i];
+      a.start[i] = plan.starts[first + i];
+    }
+    a.is_last = (first + a.count == plan.S);
+    a.end_col = plan.starts[plan.S];
+    hipLaunchKernelGGL(k_upload_table, dim3(1), dim3(kUploadBatch), 0, stream, a, tc.d_table, tc.d_starts, plan.S);
+    if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
+  }
+  tc.uploaded = true;
+  return BSGD_OK;
+}
+
+// Segments [j0, j1] that the columns [lo, hi) fall into (lo < hi, both inside the covered range).
+void segment_window(const Plan& plan, long long lo, long long hi, int* j0, int* j1) {
+  const std::vector<unsigned>& st = plan.starts;      // S + 1 ascending entries
+  *j0 = (int)(std::upper_bound(st.begin(), st.begin() + plan.S, (unsigned)lo) - st.begin()) - 1;
+  *j1 = (int)(std::upper_bound(st.begin(), st.begin() + plan.S, (unsigned)(hi - 1)) - st.begin()) - 1;
+}
+
+// Enqueue the work on `chunks` chunks of `chunk_cols` columns, one chunk per
+// workgroup, as a sequence of near-equal launches of at most
+// `rounds_per_launch` rounds of workgroups each.  With several tensors
+// (tc != null) every launch carries the segments its columns fall into as an
+// argument; only when some launch would need more than fit there, the whole
+// table goes through the workspace instead (written once per call).
 // BSGD_LAUNCH_MODE=single (environment, read once) puts everything in one
 // launch instead; kept for comparison.
-int launch(StepKernel fn, int block, long long chunks, size_t lds, hipStream_t stream, StepParams& p,
-           int rounds_per_launch = 1) {
+int launch(StepKernel fn, int block, long long chunks, long long chunk_cols, hipStream_t stream, StepParams& p,
+           TableCtx* tc, int rounds_per_launch = 1) {
   if (chunks <= 0) return BSGD_OK;
   if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   static const bool single = [] {
     const char* e = getenv("BSGD_LAUNCH_MODE");
     return e != nullptr && strcmp(e, "single") == 0;
   }();
-  long long round = single ? chunks : rounds_per_launch * round_size(fn, block, lds);
-  if (2 * chunks < 5 * round) round = chunks;        // small problems are launch-bound: one launch
-  const long long launches = (chunks + round - 1) / round;
-  const long long per = (chunks + launches - 1) / launches;
-  for (long long base = 0; base < chunks; base += per) {
-    const long long n = chunks - base < per ? chunks - base : per;
+  const bool multi = tc != nullptr;
+  // near-equal launches of one resident round (times rounds_per_launch) each; the round depends on the dynamic LDS
+  auto launch_size = [&](size_t lds) {
+    long long round = single ? chunks : rounds_per_launch * round_size(fn, block, lds);
+    if (2 * chunks < 5 * round) round = chunks;      // small problems are launch-bound: one launch
+    const long long launches = (chunks + round - 1) / round;
+    return (chunks + launches - 1) / launches;
+  };
+  // columns a launch covers, clipped to the columns that belong to tensors
+  auto span_of = [&](long long first_chunk, long long n, long long* lo, long long* hi) {
+    *lo = p.base + first_chunk * chunk_cols;
+    *hi = p.base + (first_chunk + n) * chunk_cols;
+    if (*lo < p.col_lo) *lo = p.col_lo;
+    if (*hi > p.col_hi) *hi = p.col_hi;
+  };
+  long long per = 0;
+  bool embed = multi && g_table_mode.load(std::memory_order_relaxed) == 0;
+  if (embed) {
+    per = launch_size(sizeof(unsigned) * (kEmbedSegments + 1));
+    for (long long first = 0; first < chunks && embed; first += per) {
+      long long lo, hi;
+      span_of(first, chunks - first < per ? chunks - first : per, &lo, &hi);
+      int j0, j1;
+      segment_window(*tc->plan, lo, hi, &j0, &j1);
+      if (j1 - j0 + 1 > kEmbedSegments) embed = false;
+    }
+  }
+  if (!embed) per = launch_size(multi ? sizeof(unsigned) * ((size_t)tc->plan->S + 1) : 0);
+  if (multi && !embed && !tc->uploaded) {
+    const int rc = upload_table(*tc, stream);
+    if (rc != BSGD_OK) return rc;
+  }
+
+  EmbeddedTable et;                                   // filled per launch when the table travels as an argument
+  NoTable none{};
+  for (long long first = 0; first < chunks; first += per) {
+    const long long n = chunks - first < per ? chunks - first : per;
     ++t_last_launches;
-    p.chunk_base = (int)base;
-    void* args[] = {&p};
-    hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(fn), dim3((unsigned)n), dim3(block), args, lds, stream);
+    p.chunk_base = (int)first;
+    size_t lds = 0;
+    void* second = &none;
+    if (multi) {
+      if (embed) {
+        long long lo, hi;
+        span_of(first, n, &lo, &hi);
+        int j0, j1;
+        segment_window(*tc->plan, lo, hi, &j0, &j1);
+        const int count = j1 - j0 + 1;
+        for (int i = 0; i < count; ++i) {
+          et.seg[i] = tc->plan->segs[j0 + i];
+          et.start[i] = tc->plan->starts[j0 + i];
+        }
+        et.start[count] = tc->plan->starts[j1 + 1];
+        p.table = nullptr;
+        p.starts = nullptr;
+        p.S = count;
+      } else {
+        p.table = tc->d_table;
+        p.starts = tc->d_starts;
+        p.S = tc->plan->S;
+      }
+      lds = sizeof(unsigned) * ((size_t)p.S + 1);
+      second = &et;
+    }
+    void* args[] = {&p, second};
+    hipError_t e = hipLaunchKernel(fn, dim3((unsigned)n), dim3(block), args, lds, stream);
     if (e != hipSuccess) return BSGD_ERR_HIP;
   }
   return BSGD_OK;
@@ -252,18 +359,6 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
     return 0;
   return layout(span, T, clip_on(hyper), worker_clip_on(hyper)).total;
 }
-
-// What a call will run on: the tensors as sorted, non-overlapping segments of
-// the gradient row (gaps made explicit), built and checked on the host.
-struct Plan {
-  long long span = 0;                 // largest grad_offset + numel
-  long long col_lo = 0, col_hi = 0;   // columns covered: [col_lo, col_hi)
-  int S = 0;                          // segments (S == 1: `single` is used, the vectors stay empty)
-  Segment single{};
-  bool ema = false;                   // every tensor carries a moving average
-  std::vector<Segment> segs;
-  std::vector<unsigned> starts;       // S + 1 entries
-};
 
 // Host-only validation shared by bsgd_reduce_update and bsgd_step: nothing is
 // enqueued unless this passes.
@@ -389,45 +484,28 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   if (total_chunks > L.max_chunks || total_chunks > 0x7fffffffLL) return BSGD_ERR_ARG;   // cannot happen
 
   const bool multi = plan.S > 1;
-  size_t lds = 0;
-  if (multi) {
-    Segment* d_table = reinterpret_cast<Segment*>(ws + L.table_off);
-    unsigned* d_starts = reinterpret_cast<unsigned*>(ws + L.starts_off);
-    for (int first = 0; first < plan.S; first += kUploadBatch) {
-      UploadArgs a{};
-      a.first = first;
-      a.count = (plan.S - first < kUploadBatch) ? (plan.S - first) : kUploadBatch;
-      for (int i = 0; i < a.count; ++i) {
-        a.seg[i] = plan.segs[first + i];
-        a.start[i] = plan.starts[first + i];
-      }
-      a.is_last = (first + a.count == plan.S);
-      a.end_col = plan.starts[plan.S];
-      hipLaunchKernelGGL(k_upload_table, dim3(1), dim3(kUploadBatch), 0, stream, a, d_table, d_starts, plan.S);
-      if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
-    }
-    lds = sizeof(unsigned) * ((size_t)plan.S + 1);
-  }
+  TableCtx table{&plan, reinterpret_cast<Segment*>(ws + L.table_off), reinterpret_cast<unsigned*>(ws + L.starts_off), false};
+  TableCtx* tc = multi ? &table : nullptr;
 
   const int ema = plan.ema ? 1 : 0;
   if (wclip) {
     // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
-    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc);
     if (rc != BSGD_OK) return rc;
     hipLaunchKernelGGL(k_row_scales, dim3((unsigned)N), dim3(kRowScaleBlock), 0, stream,
                        (const double*)p.row_partials, (int)total_chunks, (int)N, (int)N, (const int*)n_dev,
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p);
+  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc);
 
-  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, lds, stream, p);
+  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   // the second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails
-  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, lds, stream, p, kApplyRoundsPerLaunch);
+  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc, kApplyRoundsPerLaunch);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
@@ -543,6 +621,12 @@ int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontempo
 }
 
 int bsgd_last_launch_count(void) { return t_last_launches; }
+
+int bsgd_set_table_mode(int32_t mode) {
+  if (mode != 0 && mode != 1) return BSGD_ERR_ARG;
+  g_table_mode.store(mode, std::memory_order_relaxed);
+  return BSGD_OK;
+}
 
 int bsgd_num_shapes(void) { return kNumVariants; }
 

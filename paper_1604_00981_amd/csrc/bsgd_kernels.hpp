@@ -22,7 +22,9 @@
 #endif
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace bsgd {
 
@@ -88,9 +90,9 @@ struct StepParams {
   const WsHeader* header;    // clip_scale is read from here by k_apply
   // segments (tensors and gaps) in gradient-row column order
   Segment single;            // the one tensor when there is exactly one
-  const Segment* table;      // [S]
-  const unsigned* starts;    // [S+1] first column of each segment, then col_hi
-  int S;
+  const Segment* table;      // [S] in the workspace; null: the launch carries its part of the table as its second argument
+  const unsigned* starts;    // [S+1] first column of each segment, then the end of the last one
+  int S;                     // segments in the table this launch sees
   long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
   long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
   int chunk_base;            // chunk id of workgroup 0 of this launch
@@ -227,6 +229,37 @@ __global__ __launch_bounds__(kUploadBatch) void k_upload_table(UploadArgs a, Seg
     starts[a.first + i] = a.start[i];
   }
   if (i == 0 && a.is_last) starts[S] = a.end_col;
+}
+
+// The part of the segment table one launch needs usually fits the
+// kernel-argument buffer next to StepParams; then nothing is uploaded at all.
+// It is the second argument of the multi-tensor kernels and is read in place,
+// through the address of the argument buffer (never by name: naming it would
+// make every lane copy it to private memory).
+constexpr int kEmbedSegments = 88;                   // 88 x 32 + 89 x 4 = 3172 bytes; with StepParams under 4 KiB
+
+struct EmbeddedTable {
+  Segment seg[kEmbedSegments];                       // the segments the launch's columns fall into ...
+  unsigned start[kEmbedSegments + 1];                // ... their first columns, then the end of the last one
+};
+struct NoTable { char unused; };
+template <bool MULTI>
+using TableArg = std::conditional_t<MULTI, EmbeddedTable, NoTable>;
+
+// Where this launch's segment table is: in the workspace (p.table set), else
+// in the argument buffer right after StepParams.
+template <bool MULTI, class P>
+__device__ __forceinline__ void locate_table(const P& p, const Segment*& table, const unsigned*& starts) {
+  table = p.table;
+  starts = p.starts;
+  if constexpr (MULTI) {
+    if (p.table == nullptr) {
+      constexpr size_t at = (sizeof(P) + alignof(EmbeddedTable) - 1) / alignof(EmbeddedTable) * alignof(EmbeddedTable);
+      const char* args = (const char*)__builtin_amdgcn_kernarg_segment_ptr();
+      table = reinterpret_cast<const Segment*>(args + at + offsetof(EmbeddedTable, seg));
+      starts = reinterpret_cast<const unsigned*>(args + at + offsetof(EmbeddedTable, start));
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -442,7 +475,7 @@ __device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsig
 // float4 accesses (4-byte aligned only, since a tensor may start anywhere in
 // the row); a chunk holding a tensor boundary looks segments up per lane.
 template <int MODE, class S, bool MULTI, bool SRC_ROWS, bool EMA>
-__global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
+__global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
   constexpr int BS = S::BS, V = S::V, U = S::U;
   constexpr bool NT = S::NT;
   constexpr long long CH = 4LL * BS * V;               // columns per chunk
@@ -454,8 +487,11 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
   const float inv_n = p.div_dev != nullptr ? 1.0f / (float)*p.div_dev
                                            : (p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n);
 
+  const Segment* table;
+  const unsigned* starts;
+  locate_table<MULTI>(p, table, starts);
   if constexpr (MULTI) {
-    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
+    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = starts[i];
     __syncthreads();
   }
   const long long span_end4 = (p.col_hi + 3) & ~3LL;   // rows are readable up to here (<= ld)
@@ -473,7 +509,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
       j0 = __builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)x));
       seg_start = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[j0]);
       seg_end = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[j0 + 1]);
-      seg = p.table[j0];
+      seg = table[j0];
     } else {
       seg_start = p.col_lo;
       seg_end = p.col_hi;
@@ -546,7 +582,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
         long long lo = seg_start, hi = seg_end;
         if constexpr (MULTI) {
           if (pj != j0) {
-            sg = p.table[pj];
+            sg = table[pj];
             lo = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj]);
             hi = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj + 1]);
           }
@@ -643,7 +679,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
         for (int q = 0; q < 4; ++q) {
           sq[q] = seg;
           if constexpr (MULTI) {
-            if (ok[q]) sq[q] = p.table[jq[q]];
+            if (ok[q]) sq[q] = table[jq[q]];
           }
           ok[q] = ok[q] && sq[q].theta != nullptr;     // else: a gap
         }
@@ -691,7 +727,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p) {
 // tensor.  Same chunking and row order as k_step; rows are read U at a time.
 // Output: row_partials[chunk][row] (fp64), reduced in a fixed order.
 template <class S, bool MULTI>
-__global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p) {
+__global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p, TableArg<MULTI>) {
   constexpr int BS = S::BS, V = S::V, U = S::U;
   constexpr bool NT = S::NT;
   constexpr long long CH = 4LL * BS * V;
@@ -701,8 +737,11 @@ __global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p) {
 
   if (p.status != nullptr && *p.status != 0) return;
   const int n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
+  const Segment* table;
+  const unsigned* starts;
+  locate_table<MULTI>(p, table, starts);
   if constexpr (MULTI) {
-    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = p.starts[i];
+    for (int i = threadIdx.x; i <= p.S; i += BS) starts_lds[i] = starts[i];
     __syncthreads();
   }
   const long long span_end4 = (p.col_hi + 3) & ~3LL;
@@ -735,7 +774,7 @@ __global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p) {
       if constexpr (MULTI) {
         lo = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj]);
         hi = (long long)(unsigned)__builtin_amdgcn_readfirstlane((int)starts_lds[pj + 1]);
-        real = p.table[pj].theta != nullptr;
+        real = table[pj].theta != nullptr;
       }
       if (!real) continue;
       const long long lo_c = lo - c0, hi_c = hi - c0;

@@ -150,6 +150,15 @@ def test_tuning_rejects_unknown_shapes():
         bs.bsgd_get_shape(n)
 
 
+def test_table_mode_accepts_only_known_modes():
+    with pytest.raises(bs.BsgdError):
+        bs.bsgd_set_table_mode(2)
+    with pytest.raises(bs.BsgdError):
+        bs.bsgd_set_table_mode(-1)
+    bs.bsgd_set_table_mode(1)
+    bs.bsgd_set_table_mode(0)
+
+
 def test_build_sources_exist():
     for p in bs_build.SOURCES + bs_build.HEADERS:
         assert os.path.exists(p)

@@ -404,6 +404,45 @@ def test_every_compiled_launch_shape_gives_identical_bits():
             np.testing.assert_allclose(ac[k], bc[k], rtol=1e-6, atol=1e-9)
 
 
+def _irregular_layout(total, count, seed, crowded=0):
+    """`count` tensors of irregular sizes packed back to back over about `total` columns; with `crowded`, that many
+    tiny tensors come first (more than one launch can carry as an argument)."""
+    r = np.random.default_rng(seed)
+    sizes = [int(x) for x in r.integers(1, 90, crowded)]
+    cuts = np.sort(r.choice(np.arange(1, total), count - 1, replace=False))
+    sizes += [int(x) for x in np.diff(np.concatenate([[0], cuts, [total]]))]
+    layout, o = [], 3                                   # the first tensor does not start on a 16-byte group
+    for n in sizes:
+        layout.append((o, n))
+        o += n
+    return layout
+
+
+@pytest.mark.parametrize("crowded", [0, 200])
+@pytest.mark.parametrize("clip", [0.0, 0.004])
+def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip):
+    # 1.4 M columns go out as several launches of the narrow shape; each launch sees its own window of the table.
+    # crowded = 0: every window fits the argument buffer; crowded = 200: the first window does not, so the call
+    # writes the table into the workspace.  Forcing the workspace path must not change a bit.
+    import paper_1604_00981_amd as bs
+    layout = _irregular_layout(1_400_000, 120, seed=31, crowded=crowded)
+    results, launches = [], []
+    try:
+        for mode in (0, 1):
+            bs.bsgd_set_table_mode(mode)
+            c = Case(3, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
+            for _ in range(2):
+                c.both(*c.draw())
+            c.compare()
+            launches.append(bs.bsgd_last_launch_count())
+            results.append(c.gpu_arrays())
+    finally:
+        bs.bsgd_set_table_mode(0)
+    assert launches[0] >= 3                             # the windows differ from launch to launch
+    for k in results[0]:
+        assert np.array_equal(results[0][k], results[1][k]), k
+
+
 def test_async_server_case_N1_b0():
     # Algorithm 2's server: apply the one gradient that arrived
     c = Case(1, 0, [(0, 1030)], "sgd", seed=19)
