@@ -914,10 +914,11 @@ __global__ __launch_bounds__(S::BS) void k_precombine(CombineParams p) {
     f4 r[U][V];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int row = j + u < r1 ? j + u : r1 - 1;
-      const char* rowbase = reinterpret_cast<const char*>(p.grads + (long long)row * p.ld + c0);
+      if (j + u < r1) {                               // wave-uniform: a machine's rows are the same for every lane
+        const char* rowbase = reinterpret_cast<const char*>(p.grads + (long long)(j + u) * p.ld + c0);
 #pragma unroll
-      for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+        for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {

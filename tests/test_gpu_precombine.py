@@ -27,9 +27,11 @@ def _combine_gpu(g, t, sizes, cols, ld_out=None):
 
 @pytest.mark.parametrize("cols,ld,ld_out", [(1, 4, 4), (5, 8, 12), (8192, 8192, 8192), (20011, 20012, 20480),
                                             (70001, 70004, 70004)])
-def test_precombine_against_the_oracle(cols, ld, ld_out):
+@pytest.mark.parametrize("sizes", [[3, 1, 4, 2, 1, 5], [5, 4, 7], [1] * 16, [16]],
+                         ids=["small-machines", "large-machines", "one-worker-each", "one-machine"])
+def test_precombine_against_the_oracle(cols, ld, ld_out, sizes):
+    # machines of up to three workers on average and larger ones take different launch shapes
     r = np.random.default_rng(cols)
-    sizes = [3, 1, 4, 2, 1, 5]
     W = sum(sizes)
     g = np.zeros((W, ld), np.float32)
     g[:, :cols] = (r.standard_normal((W, cols)) * 0.01).astype(np.float32)
