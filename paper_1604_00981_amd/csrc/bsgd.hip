@@ -119,6 +119,7 @@ WsLayout layout(long long span, int T, bool clip, bool worker_clip) {
 }
 
 constexpr int kApplyRoundsPerLaunch = 8;
+constexpr int kFewRows = 8;                          // up to this many kept rows a step goes out as one launch
 std::atomic<int> g_variant{-1};                      // -1: choose by problem size
 thread_local int t_last_launches = 0;                // reduce/update launches of this thread's last call
 
@@ -488,18 +489,22 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   TableCtx* tc = multi ? &table : nullptr;
 
   const int ema = plan.ema ? 1 : 0;
+  // Rounds pay when many rows are walked in step.  With few rows the traffic is mostly theta/state, a large
+  // share of it written, and one long launch streams that faster (measured at P = 25 M: N = 1: +12..27 %,
+  // N = 4: +6..9 %, N = 8: +1 %, N = 16: -1..-7 %).
+  const int row_rounds = N <= kFewRows ? (1 << 20) : 1;
   if (wclip) {
     // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
-    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc);
+    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
     if (rc != BSGD_OK) return rc;
     hipLaunchKernelGGL(k_row_scales, dim3((unsigned)N), dim3(kRowScaleBlock), 0, stream,
                        (const double*)p.row_partials, (int)total_chunks, (int)N, (int)N, (const int*)n_dev,
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc);
+  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
 
-  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc);
+  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));

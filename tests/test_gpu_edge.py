@@ -430,7 +430,7 @@ def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip):
     try:
         for mode in (0, 1):
             bs.bsgd_set_table_mode(mode)
-            c = Case(3, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
+            c = Case(12, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
             for _ in range(2):
                 c.both(*c.draw())
             c.compare()
