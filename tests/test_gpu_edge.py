@@ -418,19 +418,21 @@ def _irregular_layout(total, count, seed, crowded=0):
     return layout
 
 
+@pytest.mark.parametrize("N", [12, 3])
 @pytest.mark.parametrize("crowded", [0, 200])
 @pytest.mark.parametrize("clip", [0.0, 0.004])
-def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip):
+def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip, N):
     # 1.4 M columns go out as several launches of the narrow shape; each launch sees its own window of the table.
     # crowded = 0: every window fits the argument buffer; crowded = 200: the first window does not, so the call
-    # writes the table into the workspace.  Forcing the workspace path must not change a bit.
+    # writes the table into the workspace.  Forcing the workspace path must not change a bit.  With N = 3 kept rows
+    # the same columns go out as one launch (few rows: no rounds), whose window holds every segment.
     import paper_1604_00981_amd as bs
     layout = _irregular_layout(1_400_000, 120, seed=31, crowded=crowded)
     results, launches = [], []
     try:
         for mode in (0, 1):
             bs.bsgd_set_table_mode(mode)
-            c = Case(12, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
+            c = Case(N, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
             for _ in range(2):
                 c.both(*c.draw())
             c.compare()
@@ -438,7 +440,10 @@ def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip):
             results.append(c.gpu_arrays())
     finally:
         bs.bsgd_set_table_mode(0)
-    assert launches[0] >= 3                             # the windows differ from launch to launch
+    if N > 8:
+        assert launches[0] >= 3                         # the windows differ from launch to launch
+    elif clip == 0.0:
+        assert launches[0] == 1
     for k in results[0]:
         assert np.array_equal(results[0][k], results[1][k]), k
 
