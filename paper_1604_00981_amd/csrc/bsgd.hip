@@ -333,7 +333,7 @@ static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bs
   }
   const int W = N + b;
   void (*fn)(const float*, int, int, SelectOpts, int*, int*, float*, int*) =
-      W <= 64 ? k_select<1> : W <= 128 ? k_select<2> : W <= 192 ? k_select<3> : k_select<4>;
+      W <= 64 ? k_select<1, true> : W <= 128 ? k_select<2, false> : W <= 192 ? k_select<3, false> : k_select<4, false>;
   hipLaunchKernelGGL(fn, dim3(1), dim3(64), 0, stream, arrival_t, (int)N, W, o, (int*)sel_idx, (int*)n_kept, t_step,
                      (int*)status);
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
