@@ -430,20 +430,19 @@ __device__ __forceinline__ void store_state(const f4& v, uintptr_t addr) {
 // theta/state update of the groups V0..V0+VN-1 of one chunk against ONE piece
 // (a tensor's column range, given relative to the chunk's first column):
 // lanes whose group lies whole inside the piece fetch theta/state together,
-// update, store; `done` collects which groups were handled.  Base addresses
+// update, store.  Base addresses
 // are wave-uniform, lanes add their byte offset.  With kClipReduce the groups
 // only add to the sum of squares.
 template <int MODE, bool EMA, class S, int V0, int VN, int V>
 __device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&toff)[V], const bool (&valid)[V],
                                              bool all, int lo_rel, int hi_rel, uintptr_t pth, uintptr_t ps0,
-                                             uintptr_t ps1, uintptr_t pe, unsigned& done, float& sumsq,
+                                             uintptr_t ps1, uintptr_t pe, float& sumsq,
                                              const StepParams& p) {
   bool in[VN];
 #pragma unroll
   for (int i = 0; i < VN; ++i) {
     const int rel = 4 * S::group_of(V0 + i);
     in[i] = all || (valid[V0 + i] && rel >= lo_rel && rel + 4 <= hi_rel);
-    done |= in[i] ? (1u << (V0 + i)) : 0u;
   }
   if constexpr (MODE == kClipReduce) {
 #pragma unroll
@@ -595,20 +594,20 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         if (valid[v]) store_state<NT>(g[v], reinterpret_cast<uintptr_t>(p.gbar + c0) + toff[v]);
     }
 
-    unsigned done = 0;                                 // bit v: group v was handled as a whole by some piece
     if (uniform) {
       // ---- the chunk lies inside one tensor (almost always): every lane, all groups at once ---
       const uintptr_t e_bytes = (uintptr_t)((c0 - seg_start) * 4);
       piece_update<MODE, EMA, S, 0, V>(g, toff, valid, true, 0, 0, reinterpret_cast<uintptr_t>(seg.theta) + e_bytes,
                                        reinterpret_cast<uintptr_t>(seg.s0) + e_bytes,
                                        reinterpret_cast<uintptr_t>(seg.s1) + e_bytes,
-                                       reinterpret_cast<uintptr_t>(seg.ema) + e_bytes, done, sumsq, p);
+                                       reinterpret_cast<uintptr_t>(seg.ema) + e_bytes, sumsq, p);
     } else {
       // ---- the chunk holds tensor boundaries, gaps or the end of the row -------------------
-      // Every group lies in at most one piece, so the pieces' loads can share
-      // one set of registers (different lanes): first all pieces fetch
-      // theta/state for the lanes they own, then everything is updated once,
-      // then all pieces store.  Groups go in two halves to bound registers.
+      // Every element lies in at most one piece, so the pieces' loads can
+      // share one set of registers: first all pieces fetch theta/state for
+      // the lanes (whole groups) and elements (groups cut by a boundary that
+      // is not a multiple of 4) they own, then everything is updated once,
+      // then all pieces store.
       auto piece = [&](int pj, Segment& sg, int& lo_rel, int& hi_rel, uintptr_t& e_bytes) {
         sg = seg;
         long long lo = seg_start, hi = seg_end;
@@ -626,6 +625,14 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         e_bytes = (uintptr_t)((c0 - lo) * 4);        // byte offset of the piece's (virtual) element at column c0
       };
       constexpr int H = BSGD_PIECE_WIDTH(V);
+      // A lane's group against a piece: 2 = wholly inside (one 16-byte access
+      // per stream), 1 = cut by the piece's edge (its elements inside the piece
+      // go one by one, to the same registers), 0 = no part of it in the piece.
+      auto inside = [&](int v, int lo_rel, int hi_rel) -> int {
+        const int rel = 4 * S::group_of(v);
+        if (!valid[v] || rel + 4 <= lo_rel || rel >= hi_rel) return 0;
+        return (rel >= lo_rel && rel + 4 <= hi_rel) ? 2 : 1;
+      };
 #pragma unroll
       for (int v0 = 0; v0 < V; v0 += H) {
         f4 th[H], a[H], b[H], e[H];
@@ -637,17 +644,29 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
             if (sg.theta == nullptr) continue;         // a gap
 #pragma unroll
             for (int i = 0; i < H; ++i) {
-              const int rel = 4 * S::group_of(v0 + i);
-              if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
-                th[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]);
-                if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]);
-                if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]);
-                if constexpr (EMA) e[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + e_bytes + toff[v0 + i]);
+              const int how = inside(v0 + i, lo_rel, hi_rel);
+              const uintptr_t at = e_bytes + toff[v0 + i];
+              if (how == 2) {
+                th[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + at);
+                if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + at);
+                if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + at);
+                if constexpr (EMA) e[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + at);
+              } else if (how == 1) {
+                const int rel = 4 * S::group_of(v0 + i);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                  if (rel + q >= lo_rel && rel + q < hi_rel) {
+                    th[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.theta) + at + 4 * q);
+                    if constexpr (MODE >= kMomentum) a[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.s0) + at + 4 * q);
+                    if constexpr (MODE == kRmspropMom) b[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.s1) + at + 4 * q);
+                    if constexpr (EMA) e[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.ema) + at + 4 * q);
+                  }
+                }
               }
             }
           }
 #pragma unroll
-          for (int i = 0; i < H; ++i) {                // lanes that own nothing: not stored
+          for (int i = 0; i < H; ++i) {                // elements that no piece owns: computed on whatever is there, never stored
             if constexpr (EMA) ema_vec(e[i], th[i], p);
             update_vec<MODE>(g[v0 + i], th[i], a[i], b[i], p);
           }
@@ -659,9 +678,9 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
           if (sg.theta == nullptr) continue;           // a gap
 #pragma unroll
           for (int i = 0; i < H; ++i) {
-            const int rel = 4 * S::group_of(v0 + i);
-            if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
-              done |= 1u << (v0 + i);
+            const int how = inside(v0 + i, lo_rel, hi_rel);
+            const uintptr_t at = e_bytes + toff[v0 + i];
+            if (how == 2) {
               if constexpr (MODE == kClipReduce) {
                 const f4 x = g[v0 + i];
                 sumsq = fmaf(x.x, x.x, sumsq);
@@ -669,78 +688,26 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
                 sumsq = fmaf(x.z, x.z, sumsq);
                 sumsq = fmaf(x.w, x.w, sumsq);
               } else {
-                *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + e_bytes + toff[v0 + i]) = th[i];
-                if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + e_bytes + toff[v0 + i]) = a[i];
-                if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + e_bytes + toff[v0 + i]) = b[i];
-                if constexpr (EMA) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + e_bytes + toff[v0 + i]) = e[i];
+                *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + at) = th[i];
+                if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + at) = a[i];
+                if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + at) = b[i];
+                if constexpr (EMA) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + at) = e[i];
               }
-            }
-          }
-        }
-      }
-      // Groups cut by a piece boundary (or lying in a gap), one per boundary
-      // that is not a multiple of 4: element by element, but with the four
-      // elements' look-ups, loads and stores each issued together.
+            } else if (how == 1) {
+              const int rel = 4 * S::group_of(v0 + i);
 #pragma unroll
-      for (int v = 0; v < V; ++v) {
-        const long long gcol = c0 + 4LL * S::group_of(v);
-        if (((done >> v) & 1u) || !valid[v] || gcol + 4 <= p.col_lo || gcol >= p.col_hi) continue;
-        bool ok[4];
-        int jq[4];
-        long long first_col[4];
-        int j = j0;
-        long long s_start = seg_start, s_end = seg_end;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const long long col = gcol + q;
-          ok[q] = col >= p.col_lo && col < p.col_hi;
-          if constexpr (MULTI) {
-            if (ok[q]) {
-              while (col >= s_end) {                   // walk the start columns on from the chunk's first piece
-                ++j;
-                s_start = s_end;
-                s_end = starts_lds[j + 1];
+              for (int q = 0; q < 4; ++q) {
+                if (rel + q >= lo_rel && rel + q < hi_rel) {
+                  if constexpr (MODE == kClipReduce) {
+                    sumsq = fmaf(g[v0 + i][q], g[v0 + i][q], sumsq);
+                  } else {
+                    *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.theta) + at + 4 * q) = th[i][q];
+                    if constexpr (MODE >= kMomentum) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.s0) + at + 4 * q) = a[i][q];
+                    if constexpr (MODE == kRmspropMom) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.s1) + at + 4 * q) = b[i][q];
+                    if constexpr (EMA) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.ema) + at + 4 * q) = e[i][q];
+                  }
+                }
               }
-            }
-          }
-          jq[q] = j;
-          first_col[q] = s_start;
-        }
-        Segment sq[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          sq[q] = seg;
-          if constexpr (MULTI) {
-            if (ok[q]) sq[q] = table[jq[q]];
-          }
-          ok[q] = ok[q] && sq[q].theta != nullptr;     // else: a gap
-        }
-        if constexpr (MODE == kClipReduce) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            if (ok[q]) sumsq = fmaf(g[v][q], g[v][q], sumsq);
-        } else {
-          float t1[4], a1[4], b1[4], e1[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            t1[q] = a1[q] = b1[q] = e1[q] = 0.f;
-            if (ok[q]) {
-              const long long e = gcol + q - first_col[q];
-              t1[q] = sq[q].theta[e];
-              if constexpr (MODE >= kMomentum) a1[q] = sq[q].s0[e];
-              if constexpr (MODE == kRmspropMom) b1[q] = sq[q].s1[e];
-              if constexpr (EMA) e1[q] = sq[q].ema[e];
-            }
-          }
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            if (ok[q]) {
-              const long long e = gcol + q - first_col[q];
-              if constexpr (EMA) sq[q].ema[e] = ema_elem(e1[q], t1[q], p);
-              update_elem<MODE>(g[v][q], t1[q], a1[q], b1[q], p);
-              sq[q].theta[e] = t1[q];
-              if constexpr (MODE >= kMomentum) sq[q].s0[e] = a1[q];
-              if constexpr (MODE == kRmspropMom) sq[q].s1[e] = b1[q];
             }
           }
         }
