@@ -414,15 +414,28 @@ __device__ __forceinline__ double block_sum(float x, float* lds) {
 // theta/state float4 at a byte address that is only known to be 4-byte
 // aligned.  They are read once and written once per step, so with NT they
 // are streamed like the gradient rows (measured: +2..4 % of bandwidth).
+//
+// The addresses are typed global-memory pointers all the way.  A pointer
+// that came out of an integer, or was read from a table in memory, is
+// "generic" to the compiler and is accessed with the generic instructions
+// and a 64-bit address register pair per access; a wave-uniform global
+// pointer plus a 32-bit lane offset needs neither (RMSProp-mom, one tensor:
+// 152 registers instead of 178).  Every theta/state pointer handed to the
+// library is device memory, so the cast is safe.
+typedef __attribute__((address_space(1))) char gbyte;
+typedef __attribute__((address_space(1))) float gfloat;
+typedef __attribute__((address_space(1))) f4u gf4u;
+__device__ __forceinline__ gbyte* bytes_of(float* q) { return (gbyte*)reinterpret_cast<char*>(q); }
+
 template <bool NT>
-__device__ __forceinline__ f4 load_state(uintptr_t addr) {
-  const f4u* q = reinterpret_cast<const f4u*>(addr);
+__device__ __forceinline__ f4 load_state(const gbyte* addr) {
+  const gf4u* q = (const gf4u*)addr;
   if constexpr (NT) return __builtin_nontemporal_load(q);
   else return *q;
 }
 template <bool NT>
-__device__ __forceinline__ void store_state(const f4& v, uintptr_t addr) {
-  f4u* q = reinterpret_cast<f4u*>(addr);
+__device__ __forceinline__ void store_state(const f4& v, gbyte* addr) {
+  gf4u* q = (gf4u*)addr;
   if constexpr (NT) __builtin_nontemporal_store(v, q);
   else *q = v;
 }
@@ -435,8 +448,8 @@ __device__ __forceinline__ void store_state(const f4& v, uintptr_t addr) {
 // only add to the sum of squares.
 template <int MODE, bool EMA, class S, int V0, int VN, int V>
 __device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&toff)[V], const bool (&valid)[V],
-                                             bool all, int lo_rel, int hi_rel, uintptr_t pth, uintptr_t ps0,
-                                             uintptr_t ps1, uintptr_t pe, float& sumsq,
+                                             bool all, int lo_rel, int hi_rel, gbyte* pth, gbyte* ps0,
+                                             gbyte* ps1, gbyte* pe, float& sumsq,
                                              const StepParams& p) {
   bool in[VN];
 #pragma unroll
@@ -573,7 +586,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
     } else {
 #pragma unroll
       for (int v = 0; v < V; ++v)
-        g[v] = load_state<NT>(reinterpret_cast<uintptr_t>(p.gbar + c0) + toff[v]) * scale;
+        g[v] = load_state<NT>(bytes_of(p.gbar + c0) + toff[v]) * scale;
     }
 
     // The segments ("pieces") the chunk's covered columns fall into: j0..j1.
@@ -591,16 +604,14 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
       // the stored mean is laid out like a row: whole groups, gaps included
 #pragma unroll
       for (int v = 0; v < V; ++v)
-        if (valid[v]) store_state<NT>(g[v], reinterpret_cast<uintptr_t>(p.gbar + c0) + toff[v]);
+        if (valid[v]) store_state<NT>(g[v], bytes_of(p.gbar + c0) + toff[v]);
     }
 
     if (uniform) {
       // ---- the chunk lies inside one tensor (almost always): every lane, all groups at once ---
-      const uintptr_t e_bytes = (uintptr_t)((c0 - seg_start) * 4);
-      piece_update<MODE, EMA, S, 0, V>(g, toff, valid, true, 0, 0, reinterpret_cast<uintptr_t>(seg.theta) + e_bytes,
-                                       reinterpret_cast<uintptr_t>(seg.s0) + e_bytes,
-                                       reinterpret_cast<uintptr_t>(seg.s1) + e_bytes,
-                                       reinterpret_cast<uintptr_t>(seg.ema) + e_bytes, sumsq, p);
+      const long long e_bytes = (c0 - seg_start) * 4;
+      piece_update<MODE, EMA, S, 0, V>(g, toff, valid, true, 0, 0, bytes_of(seg.theta) + e_bytes, bytes_of(seg.s0) + e_bytes,
+                                       bytes_of(seg.s1) + e_bytes, bytes_of(seg.ema) + e_bytes, sumsq, p);
     } else {
       // ---- the chunk holds tensor boundaries, gaps or the end of the row -------------------
       // Every element lies in at most one piece, so the pieces' loads can
@@ -608,7 +619,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
       // the lanes (whole groups) and elements (groups cut by a boundary that
       // is not a multiple of 4) they own, then everything is updated once,
       // then all pieces store.
-      auto piece = [&](int pj, Segment& sg, int& lo_rel, int& hi_rel, uintptr_t& e_bytes) {
+      auto piece = [&](int pj, Segment& sg, int& lo_rel, int& hi_rel, long long& e_bytes) {
         sg = seg;
         long long lo = seg_start, hi = seg_end;
         if constexpr (MULTI) {
@@ -622,7 +633,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         const long long lo_c = lo - c0, hi_c = hi - c0;
         lo_rel = lo_c < -8 ? -8 : (int)lo_c;
         hi_rel = hi_c > CH + 8 ? (int)(CH + 8) : (int)hi_c;
-        e_bytes = (uintptr_t)((c0 - lo) * 4);        // byte offset of the piece's (virtual) element at column c0
+        e_bytes = (c0 - lo) * 4;                     // byte offset of the piece's (virtual) element at column c0
       };
       constexpr int H = BSGD_PIECE_WIDTH(V);
       // A lane's group against a piece: 2 = wholly inside (one 16-byte access
@@ -639,27 +650,27 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         if constexpr (MODE != kClipReduce) {
 #pragma unroll 1
           for (int pj = j0; pj <= j1; ++pj) {
-            Segment sg; int lo_rel, hi_rel; uintptr_t e_bytes;
+            Segment sg; int lo_rel, hi_rel; long long e_bytes;
             piece(pj, sg, lo_rel, hi_rel, e_bytes);
             if (sg.theta == nullptr) continue;         // a gap
 #pragma unroll
             for (int i = 0; i < H; ++i) {
               const int how = inside(v0 + i, lo_rel, hi_rel);
-              const uintptr_t at = e_bytes + toff[v0 + i];
+              const long long at = e_bytes + (long long)toff[v0 + i];   // one offset from the tensor's start: inside the tensor
               if (how == 2) {
-                th[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + at);
-                if constexpr (MODE >= kMomentum) a[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + at);
-                if constexpr (MODE == kRmspropMom) b[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + at);
-                if constexpr (EMA) e[i] = *reinterpret_cast<const f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + at);
+                th[i] = *(const gf4u*)(bytes_of(sg.theta) + at);
+                if constexpr (MODE >= kMomentum) a[i] = *(const gf4u*)(bytes_of(sg.s0) + at);
+                if constexpr (MODE == kRmspropMom) b[i] = *(const gf4u*)(bytes_of(sg.s1) + at);
+                if constexpr (EMA) e[i] = *(const gf4u*)(bytes_of(sg.ema) + at);
               } else if (how == 1) {
                 const int rel = 4 * S::group_of(v0 + i);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                   if (rel + q >= lo_rel && rel + q < hi_rel) {
-                    th[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.theta) + at + 4 * q);
-                    if constexpr (MODE >= kMomentum) a[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.s0) + at + 4 * q);
-                    if constexpr (MODE == kRmspropMom) b[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.s1) + at + 4 * q);
-                    if constexpr (EMA) e[i][q] = *reinterpret_cast<const float*>(reinterpret_cast<uintptr_t>(sg.ema) + at + 4 * q);
+                    th[i][q] = *(const gfloat*)(bytes_of(sg.theta) + (at + 4 * q));
+                    if constexpr (MODE >= kMomentum) a[i][q] = *(const gfloat*)(bytes_of(sg.s0) + (at + 4 * q));
+                    if constexpr (MODE == kRmspropMom) b[i][q] = *(const gfloat*)(bytes_of(sg.s1) + (at + 4 * q));
+                    if constexpr (EMA) e[i][q] = *(const gfloat*)(bytes_of(sg.ema) + (at + 4 * q));
                   }
                 }
               }
@@ -673,13 +684,13 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         }
 #pragma unroll 1
         for (int pj = j0; pj <= j1; ++pj) {
-          Segment sg; int lo_rel, hi_rel; uintptr_t e_bytes;
+          Segment sg; int lo_rel, hi_rel; long long e_bytes;
           piece(pj, sg, lo_rel, hi_rel, e_bytes);
           if (sg.theta == nullptr) continue;           // a gap
 #pragma unroll
           for (int i = 0; i < H; ++i) {
             const int how = inside(v0 + i, lo_rel, hi_rel);
-            const uintptr_t at = e_bytes + toff[v0 + i];
+            const long long at = e_bytes + (long long)toff[v0 + i];   // one offset from the tensor's start: inside the tensor
             if (how == 2) {
               if constexpr (MODE == kClipReduce) {
                 const f4 x = g[v0 + i];
@@ -688,10 +699,10 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
                 sumsq = fmaf(x.z, x.z, sumsq);
                 sumsq = fmaf(x.w, x.w, sumsq);
               } else {
-                *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.theta) + at) = th[i];
-                if constexpr (MODE >= kMomentum) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s0) + at) = a[i];
-                if constexpr (MODE == kRmspropMom) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.s1) + at) = b[i];
-                if constexpr (EMA) *reinterpret_cast<f4u*>(reinterpret_cast<uintptr_t>(sg.ema) + at) = e[i];
+                *(gf4u*)(bytes_of(sg.theta) + at) = th[i];
+                if constexpr (MODE >= kMomentum) *(gf4u*)(bytes_of(sg.s0) + at) = a[i];
+                if constexpr (MODE == kRmspropMom) *(gf4u*)(bytes_of(sg.s1) + at) = b[i];
+                if constexpr (EMA) *(gf4u*)(bytes_of(sg.ema) + at) = e[i];
               }
             } else if (how == 1) {
               const int rel = 4 * S::group_of(v0 + i);
@@ -701,10 +712,10 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
                   if constexpr (MODE == kClipReduce) {
                     sumsq = fmaf(g[v0 + i][q], g[v0 + i][q], sumsq);
                   } else {
-                    *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.theta) + at + 4 * q) = th[i][q];
-                    if constexpr (MODE >= kMomentum) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.s0) + at + 4 * q) = a[i][q];
-                    if constexpr (MODE == kRmspropMom) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.s1) + at + 4 * q) = b[i][q];
-                    if constexpr (EMA) *reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(sg.ema) + at + 4 * q) = e[i][q];
+                    *(gfloat*)(bytes_of(sg.theta) + (at + 4 * q)) = th[i][q];
+                    if constexpr (MODE >= kMomentum) *(gfloat*)(bytes_of(sg.s0) + (at + 4 * q)) = a[i][q];
+                    if constexpr (MODE == kRmspropMom) *(gfloat*)(bytes_of(sg.s1) + (at + 4 * q)) = b[i][q];
+                    if constexpr (EMA) *(gfloat*)(bytes_of(sg.ema) + (at + 4 * q)) = e[i][q];
                   }
                 }
               }
@@ -930,7 +941,7 @@ __global__ __launch_bounds__(S::BS) void k_precombine(CombineParams p) {
   float* out = p.combined + (long long)m * p.ld_out + c0;
 #pragma unroll
   for (int v = 0; v < V; ++v)
-    if (valid[v]) store_state<NT>(acc[v], reinterpret_cast<uintptr_t>(out) + toff[v]);
+    if (valid[v]) store_state<NT>(acc[v], bytes_of(out) + toff[v]);
 }
 
 // One wavefront: machine m's message leaves with its last worker.
