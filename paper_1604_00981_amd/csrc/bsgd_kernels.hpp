@@ -316,24 +316,61 @@ __device__ __forceinline__ void fma4(f4& acc, float scale, const f4& r) {
   acc.w = fmaf(scale, r.w, acc.w);
 }
 
+// The order in which a batch's loads and adds are issued is fixed by hand
+// (the scheduling barriers), because it decides the bandwidth: the first row
+// of a batch goes out as one burst of V loads and is added as it arrives,
+// the other rows follow two loads at a time, each pair added before the next
+// is requested.  A thread then has V, then 2, loads in flight.  Issuing all
+// B*V loads before the first add is 6 % slower on every workload (measured),
+// steady pipelines of 2..8 loads per thread are 0..5 % slower; left to
+// itself the compiler picks one or the other depending on the register
+// pressure of the rest of the kernel.
 template <int V, int B, bool NT>
 __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
                                          long long colbase, const int* __restrict__ sel_idx,
                                          const float* __restrict__ row_scale, int j, const unsigned (&toff)[V]) {
-  f4 r[B][V];
+  const char* rowbase[B];
   float sc[B];
 #pragma unroll
   for (int u = 0; u < B; ++u) {
     const long long k = sel_idx[j + u];
     sc[u] = row_scale != nullptr ? row_scale[j + u] : 1.0f;   // per-worker clip scale (wave-uniform)
-    const char* rowbase = reinterpret_cast<const char*>(grads + k * ld + colbase);
-#pragma unroll
-    for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase, toff[v]);
+    rowbase[u] = reinterpret_cast<const char*>(grads + k * ld + colbase);
   }
+  if constexpr (V >= 4 && V % 2 == 0) {
+    {
+      f4 r[V];
 #pragma unroll
-  for (int u = 0; u < B; ++u)
+      for (int v = 0; v < V; ++v) r[v] = load_row_f4<NT>(rowbase[0], toff[v]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int v = 0; v < V; ++v) fma4(acc[v], sc[u], r[u][v]);
+      for (int v = 0; v < V; ++v) fma4(acc[v], sc[0], r[v]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int u = 1; u < B; ++u) {
+#pragma unroll
+      for (int v = 0; v < V; v += 2) {
+        const f4 r0 = load_row_f4<NT>(rowbase[u], toff[v]);
+        const f4 r1 = load_row_f4<NT>(rowbase[u], toff[v + 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        fma4(acc[v], sc[u], r0);
+        fma4(acc[v + 1], sc[u], r1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  } else {
+    // narrow shapes (small problems): all rows of the batch at once
+    f4 r[B][V];
+#pragma unroll
+    for (int u = 0; u < B; ++u)
+#pragma unroll
+      for (int v = 0; v < V; ++v) r[u][v] = load_row_f4<NT>(rowbase[u], toff[v]);
+#pragma unroll
+    for (int u = 0; u < B; ++u)
+#pragma unroll
+      for (int v = 0; v < V; ++v) fma4(acc[v], sc[u], r[u][v]);
+  }
 }
 
 // All kept rows, in batches of U (then 8, 4, 2, 1 for what is left).
@@ -443,19 +480,20 @@ __device__ __forceinline__ void store_state(const f4& v, gbyte* addr) {
 // theta/state update of the groups V0..V0+VN-1 of one chunk against ONE piece
 // (a tensor's column range, given relative to the chunk's first column):
 // lanes whose group lies whole inside the piece fetch theta/state together,
-// update, store.  Base addresses
+// update, store; `done` collects which groups were handled.  Base addresses
 // are wave-uniform, lanes add their byte offset.  With kClipReduce the groups
 // only add to the sum of squares.
 template <int MODE, bool EMA, class S, int V0, int VN, int V>
 __device__ __forceinline__ void piece_update(const f4 (&g)[V], const unsigned (&toff)[V], const bool (&valid)[V],
                                              bool all, int lo_rel, int hi_rel, gbyte* pth, gbyte* ps0,
-                                             gbyte* ps1, gbyte* pe, float& sumsq,
+                                             gbyte* ps1, gbyte* pe, unsigned& done, float& sumsq,
                                              const StepParams& p) {
   bool in[VN];
 #pragma unroll
   for (int i = 0; i < VN; ++i) {
     const int rel = 4 * S::group_of(V0 + i);
     in[i] = all || (valid[V0 + i] && rel >= lo_rel && rel + 4 <= hi_rel);
+    done |= in[i] ? (1u << (V0 + i)) : 0u;
   }
   if constexpr (MODE == kClipReduce) {
 #pragma unroll
@@ -607,18 +645,18 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         if (valid[v]) store_state<NT>(g[v], bytes_of(p.gbar + c0) + toff[v]);
     }
 
+    unsigned done = 0;                                 // bit v: group v was handled as a whole by some piece
     if (uniform) {
       // ---- the chunk lies inside one tensor (almost always): every lane, all groups at once ---
       const long long e_bytes = (c0 - seg_start) * 4;
       piece_update<MODE, EMA, S, 0, V>(g, toff, valid, true, 0, 0, bytes_of(seg.theta) + e_bytes, bytes_of(seg.s0) + e_bytes,
-                                       bytes_of(seg.s1) + e_bytes, bytes_of(seg.ema) + e_bytes, sumsq, p);
+                                       bytes_of(seg.s1) + e_bytes, bytes_of(seg.ema) + e_bytes, done, sumsq, p);
     } else {
       // ---- the chunk holds tensor boundaries, gaps or the end of the row -------------------
-      // Every element lies in at most one piece, so the pieces' loads can
-      // share one set of registers: first all pieces fetch theta/state for
-      // the lanes (whole groups) and elements (groups cut by a boundary that
-      // is not a multiple of 4) they own, then everything is updated once,
-      // then all pieces store.
+      // Every group lies in at most one piece, so the pieces' loads can share
+      // one set of registers (different lanes): first all pieces fetch
+      // theta/state for the lanes they own, then everything is updated once,
+      // then all pieces store.  Groups go in two halves to bound registers.
       auto piece = [&](int pj, Segment& sg, int& lo_rel, int& hi_rel, long long& e_bytes) {
         sg = seg;
         long long lo = seg_start, hi = seg_end;
@@ -636,14 +674,6 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         e_bytes = (c0 - lo) * 4;                     // byte offset of the piece's (virtual) element at column c0
       };
       constexpr int H = BSGD_PIECE_WIDTH(V);
-      // A lane's group against a piece: 2 = wholly inside (one 16-byte access
-      // per stream), 1 = cut by the piece's edge (its elements inside the piece
-      // go one by one, to the same registers), 0 = no part of it in the piece.
-      auto inside = [&](int v, int lo_rel, int hi_rel) -> int {
-        const int rel = 4 * S::group_of(v);
-        if (!valid[v] || rel + 4 <= lo_rel || rel >= hi_rel) return 0;
-        return (rel >= lo_rel && rel + 4 <= hi_rel) ? 2 : 1;
-      };
 #pragma unroll
       for (int v0 = 0; v0 < V; v0 += H) {
         f4 th[H], a[H], b[H], e[H];
@@ -655,29 +685,17 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
             if (sg.theta == nullptr) continue;         // a gap
 #pragma unroll
             for (int i = 0; i < H; ++i) {
-              const int how = inside(v0 + i, lo_rel, hi_rel);
-              const long long at = e_bytes + (long long)toff[v0 + i];   // one offset from the tensor's start: inside the tensor
-              if (how == 2) {
-                th[i] = *(const gf4u*)(bytes_of(sg.theta) + at);
-                if constexpr (MODE >= kMomentum) a[i] = *(const gf4u*)(bytes_of(sg.s0) + at);
-                if constexpr (MODE == kRmspropMom) b[i] = *(const gf4u*)(bytes_of(sg.s1) + at);
-                if constexpr (EMA) e[i] = *(const gf4u*)(bytes_of(sg.ema) + at);
-              } else if (how == 1) {
-                const int rel = 4 * S::group_of(v0 + i);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                  if (rel + q >= lo_rel && rel + q < hi_rel) {
-                    th[i][q] = *(const gfloat*)(bytes_of(sg.theta) + (at + 4 * q));
-                    if constexpr (MODE >= kMomentum) a[i][q] = *(const gfloat*)(bytes_of(sg.s0) + (at + 4 * q));
-                    if constexpr (MODE == kRmspropMom) b[i][q] = *(const gfloat*)(bytes_of(sg.s1) + (at + 4 * q));
-                    if constexpr (EMA) e[i][q] = *(const gfloat*)(bytes_of(sg.ema) + (at + 4 * q));
-                  }
-                }
+              const int rel = 4 * S::group_of(v0 + i);
+              if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
+                th[i] = *(const gf4u*)(bytes_of(sg.theta) + (e_bytes + (long long)toff[v0 + i]));
+                if constexpr (MODE >= kMomentum) a[i] = *(const gf4u*)(bytes_of(sg.s0) + (e_bytes + (long long)toff[v0 + i]));
+                if constexpr (MODE == kRmspropMom) b[i] = *(const gf4u*)(bytes_of(sg.s1) + (e_bytes + (long long)toff[v0 + i]));
+                if constexpr (EMA) e[i] = *(const gf4u*)(bytes_of(sg.ema) + (e_bytes + (long long)toff[v0 + i]));
               }
             }
           }
 #pragma unroll
-          for (int i = 0; i < H; ++i) {                // elements that no piece owns: computed on whatever is there, never stored
+          for (int i = 0; i < H; ++i) {                // lanes that own nothing: not stored
             if constexpr (EMA) ema_vec(e[i], th[i], p);
             update_vec<MODE>(g[v0 + i], th[i], a[i], b[i], p);
           }
@@ -689,9 +707,9 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
           if (sg.theta == nullptr) continue;           // a gap
 #pragma unroll
           for (int i = 0; i < H; ++i) {
-            const int how = inside(v0 + i, lo_rel, hi_rel);
-            const long long at = e_bytes + (long long)toff[v0 + i];   // one offset from the tensor's start: inside the tensor
-            if (how == 2) {
+            const int rel = 4 * S::group_of(v0 + i);
+            if (valid[v0 + i] && rel >= lo_rel && rel + 4 <= hi_rel) {
+              done |= 1u << (v0 + i);
               if constexpr (MODE == kClipReduce) {
                 const f4 x = g[v0 + i];
                 sumsq = fmaf(x.x, x.x, sumsq);
@@ -699,26 +717,78 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
                 sumsq = fmaf(x.z, x.z, sumsq);
                 sumsq = fmaf(x.w, x.w, sumsq);
               } else {
-                *(gf4u*)(bytes_of(sg.theta) + at) = th[i];
-                if constexpr (MODE >= kMomentum) *(gf4u*)(bytes_of(sg.s0) + at) = a[i];
-                if constexpr (MODE == kRmspropMom) *(gf4u*)(bytes_of(sg.s1) + at) = b[i];
-                if constexpr (EMA) *(gf4u*)(bytes_of(sg.ema) + at) = e[i];
+                *(gf4u*)(bytes_of(sg.theta) + (e_bytes + (long long)toff[v0 + i])) = th[i];
+                if constexpr (MODE >= kMomentum) *(gf4u*)(bytes_of(sg.s0) + (e_bytes + (long long)toff[v0 + i])) = a[i];
+                if constexpr (MODE == kRmspropMom) *(gf4u*)(bytes_of(sg.s1) + (e_bytes + (long long)toff[v0 + i])) = b[i];
+                if constexpr (EMA) *(gf4u*)(bytes_of(sg.ema) + (e_bytes + (long long)toff[v0 + i])) = e[i];
               }
-            } else if (how == 1) {
-              const int rel = 4 * S::group_of(v0 + i);
+            }
+          }
+        }
+      }
+      // Groups cut by a piece boundary (or lying in a gap), one per boundary
+      // that is not a multiple of 4: element by element, but with the four
+      // elements' look-ups, loads and stores each issued together.
 #pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                if (rel + q >= lo_rel && rel + q < hi_rel) {
-                  if constexpr (MODE == kClipReduce) {
-                    sumsq = fmaf(g[v0 + i][q], g[v0 + i][q], sumsq);
-                  } else {
-                    *(gfloat*)(bytes_of(sg.theta) + (at + 4 * q)) = th[i][q];
-                    if constexpr (MODE >= kMomentum) *(gfloat*)(bytes_of(sg.s0) + (at + 4 * q)) = a[i][q];
-                    if constexpr (MODE == kRmspropMom) *(gfloat*)(bytes_of(sg.s1) + (at + 4 * q)) = b[i][q];
-                    if constexpr (EMA) *(gfloat*)(bytes_of(sg.ema) + (at + 4 * q)) = e[i][q];
-                  }
-                }
+      for (int v = 0; v < V; ++v) {
+        const long long gcol = c0 + 4LL * S::group_of(v);
+        if (((done >> v) & 1u) || !valid[v] || gcol + 4 <= p.col_lo || gcol >= p.col_hi) continue;
+        bool ok[4];
+        int jq[4];
+        long long first_col[4];
+        int j = j0;
+        long long s_start = seg_start, s_end = seg_end;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const long long col = gcol + q;
+          ok[q] = col >= p.col_lo && col < p.col_hi;
+          if constexpr (MULTI) {
+            if (ok[q]) {
+              while (col >= s_end) {                   // walk the start columns on from the chunk's first piece
+                ++j;
+                s_start = s_end;
+                s_end = starts_lds[j + 1];
               }
+            }
+          }
+          jq[q] = j;
+          first_col[q] = s_start;
+        }
+        Segment sq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          sq[q] = seg;
+          if constexpr (MULTI) {
+            if (ok[q]) sq[q] = table[jq[q]];
+          }
+          ok[q] = ok[q] && sq[q].theta != nullptr;     // else: a gap
+        }
+        if constexpr (MODE == kClipReduce) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (ok[q]) sumsq = fmaf(g[v][q], g[v][q], sumsq);
+        } else {
+          float t1[4], a1[4], b1[4], e1[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            t1[q] = a1[q] = b1[q] = e1[q] = 0.f;
+            if (ok[q]) {
+              const long long e = gcol + q - first_col[q];
+              t1[q] = sq[q].theta[e];
+              if constexpr (MODE >= kMomentum) a1[q] = sq[q].s0[e];
+              if constexpr (MODE == kRmspropMom) b1[q] = sq[q].s1[e];
+              if constexpr (EMA) e1[q] = sq[q].ema[e];
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (ok[q]) {
+              const long long e = gcol + q - first_col[q];
+              if constexpr (EMA) sq[q].ema[e] = ema_elem(e1[q], t1[q], p);
+              update_elem<MODE>(g[v][q], t1[q], a1[q], b1[q], p);
+              sq[q].theta[e] = t1[q];
+              if constexpr (MODE >= kMomentum) sq[q].s0[e] = a1[q];
+              if constexpr (MODE == kRmspropMom) sq[q].s1[e] = b1[q];
             }
           }
         }
