@@ -138,15 +138,48 @@ int compute_units() {
 const Variant& pick_variant(long long total_groups) {
   const int forced = g_variant.load(std::memory_order_relaxed);
   if (forced >= 0) return kVariants[forced];
-  const long long want = 4LL * compute_units();
+  const long long cus = compute_units();
+  const long long per_round = 2 * cus;                 // resident workgroups of 256 threads at 8 wavefronts per CU
+  // Candidates: shapes whose chunks give nearly every CU two workgroups.
+  // Among them the widest chunk streams best when its launches are full, but
+  // a step is cut into launches of one round each, and a problem that is,
+  // say, 3.1 rounds wide runs 4 launches at 78 % filling.  Measured (P = 2 M
+  // .. 26 M, N = 50): bandwidth falls by 0.47 % per percent of unfilled
+  // launch, and a chunk half as wide costs 2.5 % when both are full; so the
+  // score is base - 0.47 * (1 - filling), and half-width chunks win where
+  // they fill the launches 5 points better (e.g. P = 9 M: +5.6 %, 14 M: +3 %,
+  // 2 M: +18 % over the narrow shape).  A problem that is resident all at
+  // once (one launch) is filled as evenly as its workgroups spread over the CUs.
+  const Variant* best = nullptr;
+  double best_score = -1.0;
+  int considered = 0;
   for (const Variant& v : kVariants) {
     if (!v.NT) continue;                               // plain-load shapes are for comparison only
-    if (total_groups / ((long long)v.BS * v.V) >= want) return v;
+    const long long chunks = (total_groups + (long long)v.BS * v.V - 1) / ((long long)v.BS * v.V);
+    if (v.V < 4) {                                     // narrow shapes are for small problems only
+      if (best == nullptr && chunks >= 4 * cus) best = &v;
+      if (best != nullptr) break;
+      continue;
+    }
+    const double base = 1.0 - 0.025 * considered;      // each halving of the chunk width
+    ++considered;
+    if (4 * chunks < 7 * cus) continue;
+    const long long resident = per_round * considered; // 512 of the widest shape, 1024 of the next (fewer registers)
+    double filling;
+    if (chunks <= resident) {
+      filling = (double)chunks / (double)(cus * ((chunks + cus - 1) / cus));
+    } else {
+      const long long launches = (chunks + per_round - 1) / per_round;
+      filling = (double)chunks / (double)(launches * per_round);
+    }
+    const double score = base - 0.47 * (1.0 - filling);
+    if (score > best_score) { best_score = score; best = &v; }
   }
-  int best = 0;
+  if (best != nullptr) return *best;
+  int narrowest = 0;
   for (int i = 1; i < kNumVariants; ++i)
-    if ((long long)kVariants[i].BS * kVariants[i].V < (long long)kVariants[best].BS * kVariants[best].V) best = i;
-  return kVariants[best];
+    if ((long long)kVariants[i].BS * kVariants[i].V < (long long)kVariants[narrowest].BS * kVariants[narrowest].V) narrowest = i;
+  return kVariants[narrowest];
 }
 
 // How many workgroups of `fn` one launch should hold: as many as are resident
