@@ -139,7 +139,6 @@ const Variant& pick_variant(long long total_groups) {
   const int forced = g_variant.load(std::memory_order_relaxed);
   if (forced >= 0) return kVariants[forced];
   const long long cus = compute_units();
-  const long long per_round = 2 * cus;                 // resident workgroups of 256 threads at 8 wavefronts per CU
   // Candidates: shapes whose chunks give nearly every CU two workgroups.
   // Among them the widest chunk streams best when its launches are full, but
   // a step is cut into launches of one round each, and a problem that is,
@@ -161,6 +160,7 @@ const Variant& pick_variant(long long total_groups) {
       if (best != nullptr) break;
       continue;
     }
+    const long long per_round = (512 / v.BS > 0 ? 512 / v.BS : 1) * cus;   // one round: 8 wavefronts per CU
     const double base = 1.0 - 0.025 * considered;      // each halving of the chunk width
     ++considered;
     if (4 * chunks < 7 * cus) continue;
