@@ -218,11 +218,11 @@ int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float*
  * A shape is (block, vec, unroll, nontemporal):
  *   block        threads per workgroup
  *   vec          float4 columns per thread
- *   unroll       kept rows loaded per batch before the first add
+ *   unroll       kept rows per batch of the row loop
  *   nontemporal  0/1: gradient rows are loaded with the streaming hint
  * Every shape adds the kept rows in the same order, so results do not depend
  * on it.  By default the library picks a shape from the problem size (the
- * widest chunk that still fills every compute unit several times over).
+ * chunk width whose launches fill the chip best).
  * bsgd_set_tuning pins a compiled-in shape (-1 keeps a field of the current
  * one; all four -1 returns to the automatic choice) and returns BSGD_ERR_ARG
  * when that combination is not compiled in; bsgd_num_shapes / bsgd_get_shape

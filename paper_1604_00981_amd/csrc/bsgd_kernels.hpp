@@ -36,7 +36,7 @@ typedef f4 f4u __attribute__((aligned(4)));          // float4 that is only 4-by
 //   V    float4 columns per thread (a chunk is BS*V float4 groups wide);
 //        thread t takes groups t, t+BS, ..., so each load instruction of a
 //        wavefront covers 1 KiB of contiguous row
-//   U    kept rows loaded per batch before the first add
+//   U    kept rows per batch of the row loop (see add_rows for the order of its loads and adds)
 //   NT   gradient rows are loaded with the non-temporal (streaming) hint
 template <int BS_, int V_, int U_, bool NT_>
 struct Shape {
