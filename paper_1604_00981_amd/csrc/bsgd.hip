@@ -135,7 +135,23 @@ int compute_units() {
   return cus;
 }
 
-const Variant& pick_variant(long long total_groups) {
+// Workgroups of `fn` a CU can hold at once (cached per kernel).
+int workgroups_per_cu(StepKernel fn, int block) {
+  struct Entry { StepKernel fn; int n; };
+  static std::mutex mu;
+  static std::vector<Entry> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : cache)
+    if (e.fn == fn) return e.n;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, block, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+  cache.push_back(Entry{fn, per_cu});
+  return per_cu;
+}
+
+// `kernel_of` names the kernel of a shape that does the call's main pass.
+template <class KernelOf>
+const Variant& pick_variant(long long total_groups, KernelOf&& kernel_of) {
   const int forced = g_variant.load(std::memory_order_relaxed);
   if (forced >= 0) return kVariants[forced];
   const long long cus = compute_units();
@@ -164,7 +180,7 @@ const Variant& pick_variant(long long total_groups) {
     const double base = 1.0 - 0.025 * considered;      // each halving of the chunk width
     ++considered;
     if (4 * chunks < 7 * cus) continue;
-    const long long resident = per_round * considered; // 512 of the widest shape, 1024 of the next (fewer registers)
+    const long long resident = (long long)workgroups_per_cu(kernel_of(v), v.BS) * cus;   // what one launch can hold at once
     double filling;
     if (chunks <= resident) {
       filling = (double)chunks / (double)(cus * ((chunks + cus - 1) / cus));
@@ -512,16 +528,18 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.base = plan.col_lo & ~3LL;
 
   const long long cols = ((plan.col_hi + 3) & ~3LL) - p.base;   // columns the chunks must cover
-  const Variant& var = pick_variant(cols / 4);
+  const bool multi = plan.S > 1;
+  const int ema = plan.ema ? 1 : 0;
+  const Variant& var = pick_variant(cols / 4, [&](const Variant& v) {
+    return clip ? v.reduce[multi ? 1 : 0] : v.rows[mode][multi ? 1 : 0][ema];
+  });
   const long long chunk_cols = 4LL * var.BS * var.V;
   const long long total_chunks = (cols + chunk_cols - 1) / chunk_cols;
   if (total_chunks > L.max_chunks || total_chunks > 0x7fffffffLL) return BSGD_ERR_ARG;   // cannot happen
 
-  const bool multi = plan.S > 1;
   TableCtx table{&plan, reinterpret_cast<Segment*>(ws + L.table_off), reinterpret_cast<unsigned*>(ws + L.starts_off), false};
   TableCtx* tc = multi ? &table : nullptr;
 
-  const int ema = plan.ema ? 1 : 0;
   // Rounds pay when many rows are walked in step.  With few rows the traffic is mostly theta/state, a large
   // share of it written, and one long launch streams that faster (measured at P = 25 M: N = 1: +12..27 %,
   // N = 4: +6..9 %, N = 8: +1 %, N = 16: -1..-7 %).
