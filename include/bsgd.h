@@ -193,7 +193,8 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
 /* Synchronises `stream`, then copies out what the last bsgd_step on this
  * workspace recorded.  Any out pointer may be NULL.
  *   status_out  HOST int32: BSGD_OK or BSGD_ERR_TOO_FEW
- *   t_step_out  HOST fp32: arrival time of the N-th kept gradient          */
+ *   t_step_out  HOST fp32: arrival time of the N-th kept gradient, i.e. how
+ *               long the step waited (the quantity Sec. 3.1 records)       */
 int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out);
 
 /* Synchronises `stream`, then reports how many gradients the last bsgd_step /
@@ -213,42 +214,6 @@ int bsgd_last_selection(const void* workspace, void* stream, int32_t N, int32_t*
  * clipping) and the scale applied by the last clipped step on this
  * workspace.  HOST out pointers, either may be NULL. */
 int bsgd_last_clip(const void* workspace, void* stream, double* norm_out, float* scale_out);
-
-/* Launch shape of the reduce/update kernel, process-wide; for benchmarking.
- * A shape is (block, vec, unroll, nontemporal):
- *   block        threads per workgroup
- *   vec          float4 columns per thread
- *   unroll       kept rows per batch of the row loop
- *   nontemporal  0/1: gradient rows are loaded with the streaming hint
- * Every shape adds the kept rows in the same order, so results do not depend
- * on it.  By default the library picks a shape from the problem size (the
- * chunk width whose launches fill the chip best).
- * bsgd_set_tuning pins a compiled-in shape (-1 keeps a field of the current
- * one; all four -1 returns to the automatic choice) and returns BSGD_ERR_ARG
- * when that combination is not compiled in; bsgd_num_shapes / bsgd_get_shape
- * enumerate them (out4 is HOST int32[4] in the order above). */
-int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontemporal);
-int bsgd_num_shapes(void);
-int bsgd_get_shape(int32_t i, int32_t* out4);
-
-/* How a multi-tensor call hands its tensor table to the kernels, process-wide;
- * for testing and benchmarking.  mode 0 (default): every launch carries the
- * part of the table its columns fall into as a kernel argument, and only a
- * call in which some launch touches more tensors than fit there writes the
- * whole table into the workspace first; mode 1: always through the workspace.
- * Results do not depend on it.  Returns BSGD_ERR_ARG for another mode. */
-int bsgd_set_table_mode(int32_t mode);
-
-/* How many launches of the reduce/update kernel the calling thread's last
- * bsgd_step / bsgd_reduce_update enqueued (a step is cut into launches that
- * each fill the chip once; a clipped step counts both of its passes). */
-int bsgd_last_launch_count(void);
-
-/* Measurement aid, not part of the step: a plain device-to-device copy of
- * `bytes` bytes (a multiple of 16; both pointers DEVICE, 16-byte aligned,
- * not overlapping).  It reads and writes exactly `bytes` bytes of HBM, which
- * makes it the yardstick hardware traffic counters are scaled against. */
-int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
 /* Sec. 6 of the paper: gradients of workers that share a machine are added
  * on that machine before they are sent, so the parameter side receives one

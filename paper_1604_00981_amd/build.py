@@ -10,7 +10,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libbsgd.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "bsgd.hip")]
-HEADERS = [os.path.join(PKG_DIR, "csrc", "bsgd_kernels.hpp"), os.path.join(ROOT, "include", "bsgd.h")]
+HEADERS = [os.path.join(PKG_DIR, "csrc", "bsgd_kernels.hpp"), os.path.join(ROOT, "include", "bsgd.h"),
+           os.path.join(ROOT, "include", "bsgd_debug.h")]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-shared", "-fPIC", "-std=c++17",

@@ -4,6 +4,7 @@
 #include "bsgd_kernels.hpp"
 
 #include "../../include/bsgd.h"
+#include "../../include/bsgd_debug.h"
 
 #include <algorithm>
 #include <atomic>
@@ -75,16 +76,10 @@ Variant make_variant() {
   v.rowsq[1] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, true>);
   return v;
 }
-#define BSGD_VARIANT(BS, V, U, NT) make_variant<BS, V, U, NT>()
 
-// Ordered widest chunk first (the automatic choice walks it in order).  A
-// build may supply its own list.
-#ifndef BSGD_VARIANT_LIST
-#define BSGD_VARIANT_LIST \
-  BSGD_VARIANT(256, 8, 2, 1), BSGD_VARIANT(256, 4, 2, 1), BSGD_VARIANT(256, 1, 8, 1), BSGD_VARIANT(256, 8, 2, 0)
-#endif
-
-const Variant kVariants[] = {BSGD_VARIANT_LIST};
+// Ordered widest chunk first (the automatic choice walks it in order).
+const Variant kVariants[] = {make_variant<256, 8, 2, 1>(), make_variant<256, 4, 2, 1>(), make_variant<256, 1, 8, 1>(),
+                             make_variant<256, 8, 2, 0>()};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 // Smallest chunk (in elements) over the compiled shapes: bounds the number of
@@ -283,20 +278,14 @@ void segment_window(const Plan& plan, long long lo, long long hi, int* j0, int* 
 // (tc != null) every launch carries the segments its columns fall into as an
 // argument; only when some launch would need more than fit there, the whole
 // table goes through the workspace instead (written once per call).
-// BSGD_LAUNCH_MODE=single (environment, read once) puts everything in one
-// launch instead; kept for comparison.
 int launch(StepKernel fn, int block, long long chunks, long long chunk_cols, hipStream_t stream, StepParams& p,
            TableCtx* tc, int rounds_per_launch = 1) {
   if (chunks <= 0) return BSGD_OK;
   if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
-  static const bool single = [] {
-    const char* e = getenv("BSGD_LAUNCH_MODE");
-    return e != nullptr && strcmp(e, "single") == 0;
-  }();
   const bool multi = tc != nullptr;
   // near-equal launches of one resident round (times rounds_per_launch) each; the round depends on the dynamic LDS
   auto launch_size = [&](size_t lds) {
-    long long round = single ? chunks : rounds_per_launch * round_size(fn, block, lds);
+    long long round = rounds_per_launch * round_size(fn, block, lds);
     if (2 * chunks < 5 * round) round = chunks;      // small problems are launch-bound: one launch
     const long long launches = (chunks + round - 1) / round;
     return (chunks + launches - 1) / launches;
@@ -485,9 +474,11 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
   return BSGD_OK;
 }
 
+// N: kept rows when the host knows the count (n_dev null); otherwise the count is read from n_dev on the device and
+// row_cap is the most it can be (N+b in the time-out mode).  Everything sized per kept row uses row_cap.
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
-                          const int32_t* n_dev, const int32_t* div_dev, int32_t T, const bsgd_hyper* hyper, void* workspace, const Plan& plan,
-                          hipStream_t stream) {
+                          int32_t row_cap, const int32_t* n_dev, const int32_t* div_dev, int32_t T,
+                          const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream) {
   t_last_launches = 0;
   if (plan.S == 0) return BSGD_OK;
   const int mode = hyper->opt;
@@ -507,7 +498,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   p.div_dev = div_dev;
   p.row_scale = wclip ? reinterpret_cast<const float*>(ws + L.rowscale_off) : nullptr;
   p.row_partials = reinterpret_cast<double*>(ws + L.rowpart_off);
-  p.n_stride = N;
+  p.n_stride = row_cap;                                // rows per chunk in row_partials: as many as can be kept
   p.worker_clip = hyper->worker_clip_norm;
   p.lr = hyper->lr;
   p.mu = hyper->momentum;
@@ -543,13 +534,13 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   // Rounds pay when many rows are walked in step.  With few rows the traffic is mostly theta/state, a large
   // share of it written, and one long launch streams that faster (measured at P = 25 M: N = 1: +12..27 %,
   // N = 4: +6..9 %, N = 8: +1 %, N = 16: -1..-7 %).
-  const int row_rounds = N <= kFewRows ? (1 << 20) : 1;
+  const int row_rounds = row_cap <= kFewRows ? (1 << 20) : 1;
   if (wclip) {
     // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
     int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
     if (rc != BSGD_OK) return rc;
-    hipLaunchKernelGGL(k_row_scales, dim3((unsigned)N), dim3(kRowScaleBlock), 0, stream,
-                       (const double*)p.row_partials, (int)total_chunks, (int)N, (int)N, (const int*)n_dev,
+    hipLaunchKernelGGL(k_row_scales, dim3((unsigned)row_cap), dim3(kRowScaleBlock), 0, stream,
+                       (const double*)p.row_partials, (int)total_chunks, (int)row_cap, (int)N, (const int*)n_dev,
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
@@ -571,7 +562,7 @@ int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, c
   Plan plan;
   int rc = make_plan(grads, ld, N, tensors, T, hyper, workspace, workspace_bytes, &plan);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel_idx, status, N, nullptr, nullptr, T, hyper, workspace, plan,
+  return enqueue_update(grads, ld, sel_idx, status, N, N, nullptr, nullptr, T, hyper, workspace, plan,
                         (hipStream_t)stream);
 }
 
@@ -593,7 +584,7 @@ static int step_common(const float* grads, int64_t ld, const float* arrival_t, i
   rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->n_grad, &hdr->t_step, &hdr->status,
                       (hipStream_t)stream);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? &hdr->n_kept : nullptr,
+  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? N + b : N, all_in_time ? &hdr->n_kept : nullptr,
                         counted ? &hdr->n_grad : nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
 }
 

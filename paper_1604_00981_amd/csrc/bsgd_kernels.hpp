@@ -16,11 +16,6 @@
 //   k_kth_times / k_mean_kth     time to collect k gradients (Sec. 3.1).
 #pragma once
 
-
-#ifndef BSGD_PIECE_WIDTH
-#define BSGD_PIECE_WIDTH(V) (V)
-#endif
-
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -673,7 +668,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
         hi_rel = hi_c > CH + 8 ? (int)(CH + 8) : (int)hi_c;
         e_bytes = (c0 - lo) * 4;                     // byte offset of the piece's (virtual) element at column c0
       };
-      constexpr int H = BSGD_PIECE_WIDTH(V);
+      constexpr int H = V;                             // groups per pass of the piece loops
 #pragma unroll
       for (int v0 = 0; v0 < V; v0 += H) {
         f4 th[H], a[H], b[H], e[H];

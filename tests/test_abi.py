@@ -12,19 +12,28 @@ from paper_1604_00981_amd import build as bs_build
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "bsgd.h")
+DEBUG_HEADER = os.path.join(ROOT, "include", "bsgd_debug.h")
 
 
-def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(bsgd_[a-z_0-9]+)\s*\(", text)))
+def _declared_functions(headers=(HEADER, DEBUG_HEADER)):
+    names = set()
+    for h in headers:
+        text = open(h).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(bsgd_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_entry_points():
-    names = _declared_functions()
+    names = _declared_functions((HEADER,))
     for must in ("bsgd_step", "bsgd_select_first_n", "bsgd_reduce_update", "bsgd_workspace_bytes",
                  "bsgd_last_status", "bsgd_strerror"):
         assert must in names
+    # the product header carries no tuning knob or measurement aid: those live in bsgd_debug.h
+    for aid in ("bsgd_set_tuning", "bsgd_set_table_mode", "bsgd_last_launch_count", "bsgd_calibration_copy",
+                "bsgd_num_shapes", "bsgd_get_shape"):
+        assert aid not in names
+        assert aid in _declared_functions((DEBUG_HEADER,))
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -174,7 +183,7 @@ def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
         pytest.skip("no C compiler")
     src = tmp_path / "layout.c"
     src.write_text(
-        '#include <stddef.h>\n#include <stdio.h>\n#include "bsgd.h"\n'
+        '#include <stddef.h>\n#include <stdio.h>\n#include "bsgd.h"\n#include "bsgd_debug.h"\n'
         "int main(void) {\n"
         '  printf("hyper %zu", sizeof(bsgd_hyper));\n'
         + "".join(f'  printf(" %zu", offsetof(bsgd_hyper, {f}));\n' for f, _ in bs.bsgd_hyper._fields_)

@@ -135,6 +135,14 @@ def test_c4_full_size_sampled():
     run_parity(cfg, steps=5, sample_blocks=_sample_blocks(cfg, k=6))
 
 
+def test_c4_full_size_all_elements():
+    # every element of the 300-tensor workload under the oracle, so that all of the wide shape's chunks that hold
+    # tensor boundaries (about 190 of 2930) are compared, not only those a column sample happens to hit
+    cfg = wl.get_config("C4")
+    res = run_parity(cfg, steps=2)
+    assert res.P == 24_000_429 and res.sampled == 0
+
+
 def test_c5_full_size_clipped():
     cfg = wl.get_config("C5")
     res = run_parity(cfg, steps=2)

@@ -78,6 +78,8 @@ def test_step_on_combined_messages_matches_the_oracle_pipeline(opt, clip):
         assert bs.bsgd_last_selection(c.ws, keep) == sel.tolist()
         assert bs.bsgd_last_kept_count(c.ws) == keep
         assert bs.bsgd_last_gradient_count(c.ws) == int(sum(sizes[m] for m in sel))
+        first = np.concatenate([[0], np.cumsum(sizes)])
+        c.account(g, [w for m in sel for w in range(first[m], first[m + 1])])   # the worker gradients the kept messages hold
     c.compare()
 
 
@@ -114,6 +116,7 @@ def test_deadline_mode_divides_by_the_gradients_of_every_message_in_time():
     assert bs.bsgd_last_gradient_count(c.ws) == 2 + 3 + 1 + 4
     ok, sel, _ = orc.step(g, t, 4, 2, c.otz, dict(c.hy, deadline=4.5, n_min=2, row_count=counts))
     assert ok and sel.tolist() == [0, 2, 4, 5]
+    c.account(g, sel)              # a row here stands for counts[k] gradients: the budget below is the smaller, stricter one
     c.compare()
     assert not np.array_equal(th0, c.gpu_arrays()["theta"])
 
