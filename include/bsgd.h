@@ -46,9 +46,11 @@ extern "C" {
 #define BSGD_ERR_ARG      (-1)  /* bad argument (host-detected)                     */
 #define BSGD_ERR_TOO_FEW  (-2)  /* device status: fewer than N gradients arrive     */
 #define BSGD_ERR_HIP      (-3)  /* a HIP runtime call failed                        */
+#define BSGD_ERR_SCRATCH  (-4)  /* bsgd_step_noalloc: step too large for the static scratch */
 
 #define BSGD_MAX_WORKERS  256   /* N + b may not exceed this                        */
 #define BSGD_MAX_TENSORS  4096  /* T may not exceed this                            */
+#define BSGD_STATIC_SCRATCH_BYTES 33554432  /* 32 MiB: scratch of bsgd_step_noalloc  */
 
 /* Which update rule is applied to the aggregated gradient G (Sec. 3:
  * "Sync-Opt"; Sec. 1.1 gives SGD, Appendix A.2/A.3 name RMSProp with
@@ -184,6 +186,35 @@ int bsgd_step_ex(const float* grads, int64_t ld,
                  const float* arrival_t, int32_t N, int32_t b, const bsgd_select_opts* opts,
                  const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* bsgd_step for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * bits in theta and state as bsgd_step, but the step's scratch (kept rows,
+ * tensor table, partial sums, the stored mean of a clipped step) lives in a
+ * device array of BSGD_STATIC_SCRATCH_BYTES bytes that is part of the library
+ * itself; each GPU the library runs on holds its copy until the process ends.
+ * The call allocates and frees nothing, on the device or through any library.
+ *
+ *   status   DEVICE out int32, required: BSGD_OK or BSGD_ERR_TOO_FEW (theta and
+ *            state are then untouched), written by the step's first kernel.
+ *   t_step   DEVICE out fp32 or NULL: arrival time of the N-th kept gradient.
+ *
+ * Limit: bsgd_workspace_bytes(span, N, b, T, hyper) must not exceed
+ * BSGD_STATIC_SCRATCH_BYTES, else BSGD_ERR_SCRATCH is returned and nothing is
+ * enqueued.  Steps without clipping always fit (under 0.4 MiB for 4096
+ * tensors); a step clipped by the global norm fits up to about 8.2 M columns,
+ * with per-worker clipping up to about 16 M, with both up to about 5.5 M.
+ * All calls on one GPU share that GPU's array: two calls whose kernels can
+ * overlap in time (different streams without an ordering between them, or
+ * different host threads) race on it and must be serialised by the caller.
+ * The array's address on the current device is looked up on the first call on
+ * that device; make that call outside graph capture.  The bsgd_last_* getters
+ * do not apply (there is no workspace pointer to give them). */
+int bsgd_step_noalloc(const float* grads, int64_t ld,
+                      const float* arrival_t, int32_t N, int32_t b,
+                      const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
+                      int32_t* status, float* t_step, void* stream);
 
 /* Bytes of workspace bsgd_step / bsgd_reduce_update need.  span = the largest
  * grad_offset + numel over the tensors (the total parameter count when the

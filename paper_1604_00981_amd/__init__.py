@@ -2,7 +2,8 @@
 (Algorithm 4 of "Revisiting Distributed Synchronous SGD") as hand-written HIP
 kernels for MI355X behind a C ABI (include/bsgd.h), plus this thin binding."""
 from .binding import (  # noqa: F401
-    BSGD_OK, BSGD_ERR_ARG, BSGD_ERR_TOO_FEW, BSGD_ERR_HIP, BSGD_MAX_WORKERS, BSGD_MAX_TENSORS,
+    BSGD_OK, BSGD_ERR_ARG, BSGD_ERR_TOO_FEW, BSGD_ERR_HIP, BSGD_ERR_SCRATCH, BSGD_STATIC_SCRATCH_BYTES,
+    BSGD_MAX_WORKERS, BSGD_MAX_TENSORS, bsgd_step_noalloc,
     BSGD_SGD, BSGD_MOMENTUM, BSGD_RMSPROP_MOM,
     BsgdError, bsgd_hyper, bsgd_tensor, bsgd_select_opts, make_select_opts,
     bsgd_select_ex, bsgd_step_ex, bsgd_last_kept_count,

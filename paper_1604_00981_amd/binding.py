@@ -20,6 +20,8 @@ BSGD_OK = 0
 BSGD_ERR_ARG = -1
 BSGD_ERR_TOO_FEW = -2
 BSGD_ERR_HIP = -3
+BSGD_ERR_SCRATCH = -4
+BSGD_STATIC_SCRATCH_BYTES = 33554432
 BSGD_MAX_WORKERS = 256
 BSGD_MAX_TENSORS = 4096
 
@@ -72,6 +74,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_step.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_tensor), i32,
                               ctypes.POINTER(bsgd_hyper), vp, sz, vp]
     lib.bsgd_step.restype = ctypes.c_int
+    lib.bsgd_step_noalloc.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_tensor), i32,
+                                      ctypes.POINTER(bsgd_hyper), vp, vp, vp]
+    lib.bsgd_step_noalloc.restype = ctypes.c_int
     lib.bsgd_select_ex.argtypes = [vp, i32, i32, ctypes.POINTER(bsgd_select_opts), vp, vp, vp, vp, vp]
     lib.bsgd_select_ex.restype = ctypes.c_int
     lib.bsgd_step_ex.argtypes = [vp, i64, vp, i32, i32, ctypes.POINTER(bsgd_select_opts), ctypes.POINTER(bsgd_tensor), i32,
@@ -226,6 +231,15 @@ def bsgd_step(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, tensors
     ws, nbytes = _ws(workspace, workspace_bytes)
     _check(lib.bsgd_step(_ptr(grads, torch.float32, "grads"), ld, _ptr(arrival_t, torch.float32, "arrival_t"),
                          N, b, tensors, len(tensors), ctypes.byref(hyper), ws, nbytes, _stream(stream)), "bsgd_step")
+
+
+def bsgd_step_noalloc(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, tensors, hyper: bsgd_hyper,
+                      status: DevPtr, t_step: DevPtr = None, stream=None) -> None:
+    """bsgd_step on the library's own static device scratch (no workspace argument, nothing allocated)."""
+    lib = load_library()
+    _check(lib.bsgd_step_noalloc(_ptr(grads, torch.float32, "grads"), ld, _ptr(arrival_t, torch.float32, "arrival_t"),
+                                 N, b, tensors, len(tensors), ctypes.byref(hyper), _ptr(status, torch.int32, "status"),
+                                 _ptr(t_step, torch.float32, "t_step"), _stream(stream)), "bsgd_step_noalloc")
 
 
 def bsgd_step_ex(grads: DevPtr, ld: int, arrival_t: DevPtr, N: int, b: int, opts: bsgd_select_opts, tensors,

@@ -402,7 +402,8 @@ size_t bsgd_workspace_bytes(int64_t span, int32_t N, int32_t b, int32_t T, const
 // Host-only validation shared by bsgd_reduce_update and bsgd_step: nothing is
 // enqueued unless this passes.
 static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tensor* tensors, int32_t T,
-                     const bsgd_hyper* hyper, const void* workspace, size_t workspace_bytes, Plan* plan) {
+                     const bsgd_hyper* hyper, const void* workspace, size_t workspace_bytes, Plan* plan,
+                     int too_small_code = BSGD_ERR_ARG) {
   if (grads == nullptr || tensors == nullptr || hyper == nullptr || workspace == nullptr) return BSGD_ERR_ARG;
   if (N < 1 || N > BSGD_MAX_WORKERS || T < 1 || T > BSGD_MAX_TENSORS || ld < 0) return BSGD_ERR_ARG;
   if (hyper->opt < BSGD_SGD || hyper->opt > BSGD_RMSPROP_MOM) return BSGD_ERR_ARG;
@@ -434,7 +435,7 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
   plan->ema = with_ema != 0;
   if (span >= 0xFFFFFFF0LL) return BSGD_ERR_ARG;       // segment starts are kept as 32-bit columns
   const WsLayout L = layout(span, T, clip_on(hyper), worker_clip_on(hyper));
-  if (workspace_bytes < L.total) return BSGD_ERR_ARG;
+  if (workspace_bytes < L.total) return too_small_code;
   plan->span = span;
   plan->S = 0;
   if (live == 0) return BSGD_OK;                       // nothing to update
@@ -566,9 +567,12 @@ int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, c
                         (hipStream_t)stream);
 }
 
+// status_out / t_step_out: where the selection writes the status word and the waiting time, and where the later
+// kernels read the status from; null: the workspace header.
 static int step_common(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
                        const bsgd_select_opts* opts, const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+                       void* workspace, size_t workspace_bytes, void* stream, int32_t* status_out = nullptr,
+                       float* t_step_out = nullptr, int too_small_code = BSGD_ERR_ARG) {
   if (!check_select_args(arrival_t, N, b)) return BSGD_ERR_ARG;
   if (opts != nullptr && (opts->n_min < 0 || opts->n_min > N + b || opts->deadline != opts->deadline)) return BSGD_ERR_ARG;
   const bool counted = opts != nullptr && opts->row_count != nullptr;
@@ -576,15 +580,17 @@ static int step_common(const float* grads, int64_t ld, const float* arrival_t, i
   Plan plan;
   // in deadline mode up to N+b rows may be kept
   const bool all_in_time = opts != nullptr && opts->n_min > 0;
-  int rc = make_plan(grads, ld, all_in_time ? N + b : N, tensors, T, hyper, workspace, workspace_bytes, &plan);
+  int rc = make_plan(grads, ld, all_in_time ? N + b : N, tensors, T, hyper, workspace, workspace_bytes, &plan,
+                     too_small_code);
   if (rc != BSGD_OK) return rc;
   char* ws = static_cast<char*>(workspace);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(ws);
   int* sel = reinterpret_cast<int*>(ws + kAlign);
-  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->n_grad, &hdr->t_step, &hdr->status,
-                      (hipStream_t)stream);
+  int32_t* status = status_out != nullptr ? status_out : &hdr->status;
+  float* t_step = status_out != nullptr ? t_step_out : &hdr->t_step;
+  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->n_grad, t_step, status, (hipStream_t)stream);
   if (rc != BSGD_OK) return rc;
-  return enqueue_update(grads, ld, sel, &hdr->status, N, all_in_time ? N + b : N, all_in_time ? &hdr->n_kept : nullptr,
+  return enqueue_update(grads, ld, sel, status, N, all_in_time ? N + b : N, all_in_time ? &hdr->n_kept : nullptr,
                         counted ? &hdr->n_grad : nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
 }
 
@@ -599,6 +605,47 @@ int bsgd_step_ex(const float* grads, int64_t ld, const float* arrival_t, int32_t
                  void* workspace, size_t workspace_bytes, void* stream) {
   if (opts == nullptr) return BSGD_ERR_ARG;
   return step_common(grads, ld, arrival_t, N, b, opts, tensors, T, hyper, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------
+// bsgd_step for callers that cannot hand over (or allocate) a workspace: the
+// step's scratch lives in a device array that is part of this library's code
+// object.  Each GPU holds its own copy at its own address from the moment the
+// library's device code is loaded there until the process ends.
+// ---------------------------------------------------------------------------
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[BSGD_STATIC_SCRATCH_BYTES];
+
+// In host code the name `scratch` is only a handle for the runtime's symbol
+// table; the array's device address is asked for once per device, with that
+// device current, and kept.
+constexpr int kMaxDevices = 64;
+static int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BSGD_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr_of_device[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return BSGD_ERR_HIP;
+    if ((reinterpret_cast<uintptr_t>(ptr) & (kAlign - 1)) != 0) return BSGD_ERR_HIP;
+    ptr_of_device[dev] = ptr;
+  }
+  *out = ptr_of_device[dev];
+  return BSGD_OK;
+}
+
+int bsgd_step_noalloc(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
+                      const bsgd_tensor* tensors, int32_t T, const bsgd_hyper* hyper, int32_t* status, float* t_step,
+                      void* stream) {
+  if (status == nullptr) return BSGD_ERR_ARG;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != BSGD_OK) return rc;
+  // Nothing in the array has to start at zero: every word a kernel of the step reads (status, kept rows, table,
+  // partial sums, stored mean) is written earlier in the same step, so what the last call left behind is never seen.
+  return step_common(grads, ld, arrival_t, N, b, nullptr, tensors, T, hyper, ws, (size_t)BSGD_STATIC_SCRATCH_BYTES,
+                     stream, status, t_step, BSGD_ERR_SCRATCH);
 }
 
 int bsgd_last_status(const void* workspace, void* stream, int32_t* status_out, float* t_step_out) {
@@ -816,6 +863,7 @@ const char* bsgd_strerror(int code) {
     case BSGD_ERR_ARG: return "invalid argument";
     case BSGD_ERR_TOO_FEW: return "fewer than N gradients arrived; parameters left untouched";
     case BSGD_ERR_HIP: return "HIP runtime call failed";
+    case BSGD_ERR_SCRATCH: return "the step needs more scratch memory than the library's static buffer holds";
     default: return "unknown bsgd code";
   }
 }
