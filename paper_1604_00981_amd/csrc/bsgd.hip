@@ -229,6 +229,37 @@ struct Plan {
 };
 
 
+// A run of consecutive chunks of which each (but for a few) holds columns of
+// some tensor.  A call whose tensors leave wide gaps in the row (a
+// partial-range update: only some layers' gradients are in) is enqueued run
+// by run, so the gaps cost neither workgroups nor row reads.
+struct Run { long long first, count; };
+
+// Gaps narrower than this many chunks stay inside a run (their chunks are
+// launched and stand down on the device before reading any row): a launch
+// boundary costs more than a few idle workgroups.
+constexpr long long kMergeGapChunks = 64;
+
+std::vector<Run> chunk_runs(const Plan& plan, long long base, long long chunk_cols, long long total_chunks) {
+  std::vector<Run> runs;
+  if (plan.S <= 1) {
+    runs.push_back(Run{0, total_chunks});
+    return runs;
+  }
+  for (int j = 0; j < plan.S; ++j) {
+    if (plan.segs[j].theta == nullptr) continue;       // a gap
+    const long long c_first = ((long long)plan.starts[j] - base) / chunk_cols;
+    const long long c_last = ((long long)plan.starts[j + 1] - 1 - base) / chunk_cols;
+    if (!runs.empty() && c_first <= runs.back().first + runs.back().count + kMergeGapChunks) {
+      const long long end = runs.back().first + runs.back().count;
+      if (c_last + 1 > end) runs.back().count = c_last + 1 - runs.back().first;
+    } else {
+      runs.push_back(Run{c_first, c_last - c_first + 1});
+    }
+  }
+  return runs;
+}
+
 // The segment table of a multi-tensor call during one enqueue_update: where
 // the workspace copy lives and whether this call has written it yet.
 struct TableCtx {
@@ -278,10 +309,12 @@ void segment_window(const Plan& plan, long long lo, long long hi, int* j0, int* 
 // (tc != null) every launch carries the segments its columns fall into as an
 // argument; only when some launch would need more than fit there, the whole
 // table goes through the workspace instead (written once per call).
-int launch(StepKernel fn, int block, long long chunks, long long chunk_cols, hipStream_t stream, StepParams& p,
-           TableCtx* tc, int rounds_per_launch = 1) {
+// The chunks are first_chunk .. first_chunk+chunks-1 of the call's column
+// space; their slots in the per-chunk partial-sum arrays start at first_slot.
+int launch(StepKernel fn, int block, long long first_chunk, long long first_slot, long long chunks,
+           long long chunk_cols, hipStream_t stream, StepParams& p, TableCtx* tc, int rounds_per_launch = 1) {
   if (chunks <= 0) return BSGD_OK;
-  if (chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
+  if (first_chunk + chunks > 0x7fffffffLL || first_slot + chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   const bool multi = tc != nullptr;
   // near-equal launches of one resident round (times rounds_per_launch) each; the round depends on the dynamic LDS
   auto launch_size = [&](size_t lds) {
@@ -291,9 +324,9 @@ int launch(StepKernel fn, int block, long long chunks, long long chunk_cols, hip
     return (chunks + launches - 1) / launches;
   };
   // columns a launch covers, clipped to the columns that belong to tensors
-  auto span_of = [&](long long first_chunk, long long n, long long* lo, long long* hi) {
-    *lo = p.base + first_chunk * chunk_cols;
-    *hi = p.base + (first_chunk + n) * chunk_cols;
+  auto span_of = [&](long long first, long long n, long long* lo, long long* hi) {
+    *lo = p.base + (first_chunk + first) * chunk_cols;
+    *hi = p.base + (first_chunk + first + n) * chunk_cols;
     if (*lo < p.col_lo) *lo = p.col_lo;
     if (*hi > p.col_hi) *hi = p.col_hi;
   };
@@ -320,7 +353,8 @@ int launch(StepKernel fn, int block, long long chunks, long long chunk_cols, hip
   for (long long first = 0; first < chunks; first += per) {
     const long long n = chunks - first < per ? chunks - first : per;
     ++t_last_launches;
-    p.chunk_base = (int)first;
+    p.chunk_base = (int)(first_chunk + first);
+    p.slot_base = (int)(first_slot + first);
     size_t lds = 0;
     void* second = &none;
     if (multi) {
@@ -522,7 +556,11 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   const long long cols = ((plan.col_hi + 3) & ~3LL) - p.base;   // columns the chunks must cover
   const bool multi = plan.S > 1;
   const int ema = plan.ema ? 1 : 0;
-  const Variant& var = pick_variant(cols / 4, [&](const Variant& v) {
+  // the shape is chosen for the columns that belong to tensors: wide gaps are neither launched nor read
+  long long covered = plan.col_hi - plan.col_lo;
+  for (int j = 0; j < (multi ? plan.S : 0); ++j)
+    if (plan.segs[j].theta == nullptr) covered -= (long long)plan.starts[j + 1] - (long long)plan.starts[j];
+  const Variant& var = pick_variant((covered + 3) / 4, [&](const Variant& v) {
     return clip ? v.reduce[multi ? 1 : 0] : v.rows[mode][multi ? 1 : 0][ema];
   });
   const long long chunk_cols = 4LL * var.BS * var.V;
@@ -536,24 +574,37 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   // share of it written, and one long launch streams that faster (measured at P = 25 M: N = 1: +12..27 %,
   // N = 4: +6..9 %, N = 8: +1 %, N = 16: -1..-7 %).
   const int row_rounds = row_cap <= kFewRows ? (1 << 20) : 1;
+  // only chunks that hold columns of some tensor are launched; the per-chunk partial sums are indexed by launch order
+  const std::vector<Run> runs = chunk_runs(plan, p.base, chunk_cols, total_chunks);
+  long long slots = 0;
+  for (const Run& r : runs) slots += r.count;
+  auto launch_runs = [&](StepKernel fn, int rounds) {
+    long long slot = 0;
+    for (const Run& r : runs) {
+      const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, rounds);
+      if (rc != BSGD_OK) return rc;
+      slot += r.count;
+    }
+    return (int)BSGD_OK;
+  };
   if (wclip) {
     // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
-    int rc = launch(var.rowsq[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
+    int rc = launch_runs(var.rowsq[multi ? 1 : 0], row_rounds);
     if (rc != BSGD_OK) return rc;
     hipLaunchKernelGGL(k_row_scales, dim3((unsigned)row_cap), dim3(kRowScaleBlock), 0, stream,
-                       (const double*)p.row_partials, (int)total_chunks, (int)row_cap, (int)N, (const int*)n_dev,
+                       (const double*)p.row_partials, (int)slots, (int)row_cap, (int)N, (const int*)n_dev,
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  if (!clip) return launch(var.rows[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
+  if (!clip) return launch_runs(var.rows[mode][multi ? 1 : 0][ema], row_rounds);
 
-  int rc = launch(var.reduce[multi ? 1 : 0], var.BS, total_chunks, chunk_cols, stream, p, tc, row_rounds);
+  int rc = launch_runs(var.reduce[multi ? 1 : 0], row_rounds);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
-                     (int)total_chunks, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
+                     (int)slots, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   // the second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails
-  return launch(var.apply[mode][multi ? 1 : 0][ema], var.BS, total_chunks, chunk_cols, stream, p, tc, kApplyRoundsPerLaunch);
+  return launch_runs(var.apply[mode][multi ? 1 : 0][ema], kApplyRoundsPerLaunch);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,

@@ -91,6 +91,8 @@ struct StepParams {
   long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
   long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
   int chunk_base;            // chunk id of workgroup 0 of this launch
+  int slot_base;             // index of workgroup 0's slot in partials / row_partials (chunks that hold no tensor
+                             // are not launched and have no slot)
 };
 
 // ---------------------------------------------------------------------------
@@ -594,6 +596,24 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
     }
     const bool uniform = (c0 >= seg_start) && (c0 + CH <= seg_end) && (seg.theta != nullptr);
 
+    // A chunk that lies wholly in a gap between tensors (a partial-range update
+    // names only some layers) has nothing to do: no row of it is read.  Gaps
+    // and tensors alternate in the table, so the chunk holds a tensor unless
+    // its first piece is a gap and also its last one.
+    if constexpr (MULTI) {
+      if (seg.theta == nullptr) {
+        long long last = c0 + CH - 1;
+        if (last >= p.col_hi) last = p.col_hi - 1;
+        if (last < p.col_lo) last = p.col_lo;
+        if (__builtin_amdgcn_readfirstlane(find_segment(starts_lds, p.S, (unsigned)last)) == j0) {
+          if constexpr (MODE == kClipReduce) {
+            if (threadIdx.x == 0) p.partials[(int)blockIdx.x + p.slot_base] = 0.0;
+          }
+          return;
+        }
+      }
+    }
+
     float scale = 1.0f;
     if constexpr (!SRC_ROWS) scale = p.header->clip_scale;
     float sumsq = 0.0f;
@@ -792,7 +812,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
 
     if constexpr (MODE == kClipReduce) {
       const double s = block_sum<BS>(sumsq, red_lds);
-      if (threadIdx.x == 0) p.partials[chunk_id] = s;
+      if (threadIdx.x == 0) p.partials[(int)blockIdx.x + p.slot_base] = s;
     }
   }
 }
@@ -865,6 +885,17 @@ __global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p, TableArg<MULT
     }
   }
 
+  const int slot = (int)blockIdx.x + p.slot_base;
+  {
+    // a chunk that holds no tensor column adds nothing to any norm: its rows are not read
+    unsigned any = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v) any |= member[v];
+    if (!__syncthreads_or((int)any)) {
+      for (int row = threadIdx.x; row < n_rows; row += BS) p.row_partials[(long long)slot * p.n_stride + row] = 0.0;
+      return;
+    }
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int j = 0; j < n_rows; j += U) {
     f4 r[U][V];
@@ -896,7 +927,7 @@ __global__ __launch_bounds__(S::BS) void k_row_sumsq(StepParams p, TableArg<MULT
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) s += (double)wave_part[row][w];
-    p.row_partials[(long long)chunk_id * p.n_stride + row] = s;
+    p.row_partials[(long long)slot * p.n_stride + row] = s;
   }
 }
 

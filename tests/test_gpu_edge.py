@@ -307,6 +307,48 @@ def test_tensors_listed_out_of_order_with_gaps():
     cc.compare()
 
 
+@pytest.mark.parametrize("kind", ["plain", "clip", "worker_clip", "ema_clip"])
+@pytest.mark.parametrize("gap", [200_003, 1_100_001])
+def test_wide_gaps_between_tensors_are_neither_launched_nor_read(kind, gap):
+    # A partial-range update (Appendix A.3: top layers' gradients are sent while the lower layers are still being
+    # computed) names only the tensors whose gradients are in.  The columns in between are NaN here: no chunk that
+    # lies wholly in a gap may be read, in any launch shape.  The narrow gap stays inside one run of chunks in the
+    # wide shapes (its workgroups stand down on the device), the wide one splits the call into two runs.
+    import paper_1604_00981_amd as bs
+    hyper = dict(plain={}, clip=dict(clip_norm=0.004), worker_clip=dict(worker_clip_norm=1.4),
+                 ema_clip=dict(clip_norm=0.004))[kind]
+    layout = [(5, 30_001), (30_006, 2_000), (32_006 + gap, 20_003)]
+    shapes = [bs.bsgd_get_shape(i) for i in range(bs.bsgd_num_shapes())]
+    results = []
+    try:
+        for shape in shapes:
+            bs.bsgd_set_tuning(*shape)
+            c = Case(6, 2, layout, "rmsprop_mom" if kind != "worker_clip" else "momentum", seed=91, theta_shift=1,
+                     hyper=hyper, ema=0.9 if kind == "ema_clip" else None)
+            covered = np.zeros(c.ld, bool)
+            for o, n in layout:
+                covered[o:o + n] = True
+            for _ in range(2):
+                g, t = c.draw()
+                g *= c.r.uniform(0.3, 3.0, (c.W, 1)).astype(np.float32)
+                g[:, ~covered] = np.nan
+                assert c.both(g, t) == 0
+            c.compare()
+            chunk_cols = 4 * shape[0] * shape[1]
+            passes = {"plain": 1, "clip": 2, "worker_clip": 2, "ema_clip": 2}[kind]
+            if gap // chunk_cols > 64 + 1:
+                assert bs.bsgd_last_launch_count() == 2 * passes      # one launch per run and pass: the gap is not launched
+            else:
+                assert bs.bsgd_last_launch_count() == passes          # one run; gap chunks stand down on the device
+            results.append(c.gpu_arrays())
+    finally:
+        bs.bsgd_set_tuning()
+    if kind == "plain":
+        for a, bb in zip(results, results[1:]):
+            for k in a:
+                assert np.array_equal(a[k], bb[k]), k
+
+
 def test_many_tensors_multiple_upload_batches_and_empty_ones():
     r = np.random.default_rng(5)
     sizes = [int(x) for x in r.integers(0, 700, 333)]          # some are empty

@@ -143,6 +143,19 @@ def test_c4_full_size_all_elements():
     assert res.P == 24_000_429 and res.sampled == 0
 
 
+def test_c4_full_size_moving_average_sampled():
+    cfg = wl.get_config("C4")
+    run_parity(cfg, steps=3, sample_blocks=_sample_blocks(cfg, k=8, seed=1), ema_decay=0.9999)
+
+
+def test_c2_full_size_per_worker_clip_all_elements():
+    # each kept gradient clipped by its own norm over all 25 M columns (the per-row sums of squares in the launch
+    # shape the benchmark times), then the fused update; the norms couple every element, so the oracle runs in full.
+    # ||G_k|| ~ s_k * 1e-3 * sqrt(P) with s_k in [0.5, 1.5]: a threshold at s = 1 clips about half of the workers
+    cfg = wl.get_config("C2")
+    run_parity(cfg, steps=2, worker_clip=float(1e-3 * np.sqrt(cfg.P)))
+
+
 def test_c5_full_size_clipped():
     cfg = wl.get_config("C5")
     res = run_parity(cfg, steps=2)
