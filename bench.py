@@ -111,6 +111,45 @@ def measured_traffic(plain_c2: bool):
         return None
 
 
+def yardstick_main(args, bs) -> int:
+    """Plain streaming kernels with the stream mixes of the step's passes (bsgd_yardstick_streams): what the memory
+    system gives a kernel that only moves those streams.  One JSON line; every entry is GB/s of bytes moved."""
+    import torch
+    reps, warm = max(3, args.steps), max(1, args.warmup)
+
+    def run(label, n_floats, n_read, n_write, vec, in_place=True):
+        bufs = [torch.full((n_floats,), 0.25, device="cuda") for _ in range(max(n_read, n_write if not in_place else 0))]
+        outs = bufs[:n_write] if in_place else [torch.empty(n_floats, device="cuda") for _ in range(n_write)]
+        nbytes = n_floats * 4
+        for _ in range(warm):
+            bs.bsgd_yardstick_streams(bufs[:n_read], outs, nbytes, vec)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            bs.bsgd_yardstick_streams(bufs[:n_read], outs, nbytes, vec)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        moved = (n_read + n_write) * nbytes
+        del bufs, outs
+        return {"mix": label, "streams_read": n_read, "streams_written": n_write, "MB_per_stream": round(nbytes / 1e6, 1),
+                "groups_per_thread": vec, "ms": round(ms, 5), "GB/s": round(moved / (ms * 1e-3) / 1e9, 1),
+                "frac_of_peak": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    P2, P5 = 25_000_000, 134_217_728
+    rows = []
+    for vec in (8, 1):
+        rows.append(run("read only, one 5.4 GB buffer (the kept rows of C2)", 54 * P2, 1, 0, vec))
+        rows.append(run("update of C2: theta, ms, m read and written in place", P2, 3, 3, vec))
+        rows.append(run("pass 2 of a clipped step at C5's size: stored mean, theta, v read; theta, v written", P5, 3, 2, vec))
+        rows.append(run("pre-combine of pairs: two rows read, one written", P2, 2, 1, vec, in_place=False))
+        rows.append(run("copy: one read, one written", P5, 1, 1, vec, in_place=False))
+    print(json.dumps({"metric": "yardstick streaming kernels (bsgd_yardstick_streams)", "unit": "GB/s", "n_gpus": 1,
+                      "steps": reps, "warmup": warm, "peak": HBM_PEAK_GBS, "data": "synthetic", "results": rows}))
+    return 0
+
+
 def precombine_main(args, bs, wl) -> int:
     """Times bsgd_precombine on the workload's gradient matrix, machines of G consecutive workers."""
     import numpy as np
@@ -217,6 +256,14 @@ def main() -> int:
     ap.add_argument("--precombine", type=int, default=0, metavar="G",
                     help="time bsgd_precombine (one message per machine of G workers) on the workload's gradient "
                          "matrix instead of the step; not the headline workload")
+    ap.add_argument("--separate-selection", action="store_true",
+                    help="always run the selection as a kernel of its own (small steps otherwise do it inside their "
+                         "one launch); for comparison")
+    ap.add_argument("--yardstick", action="store_true",
+                    help="time plain streaming kernels with the stream mixes of the step's passes instead of the step")
+    ap.add_argument("--gap", type=int, default=0, metavar="COLUMNS",
+                    help="leave a gap of this many columns in the middle of the gradient rows (a partial-range update: "
+                         "the second half of the tensors sits after the gap); exploration, not the headline workload")
     ap.add_argument("--straggler-iterations", type=int, default=0, metavar="B",
                     help="time the straggler analysis (time to collect k gradients over B recorded iterations of "
                          "100 machines) instead of the step; not the headline workload")
@@ -237,6 +284,11 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.tuning:
         bs.bsgd_set_tuning(*[int(x) for x in args.tuning.split(",")])
+    if args.separate_selection:
+        bs.bsgd_set_fused_selection(False)
+
+    if args.yardstick:
+        return yardstick_main(args, bs)
 
     if args.straggler_iterations > 0:
         return straggler_main(args, bs, wl)
@@ -248,8 +300,16 @@ def main() -> int:
     offs, sizes, P = wl.tensor_layout(cfg)
     T, N, b, W = len(sizes), cfg.N, cfg.b, cfg.W
     K, Wm = args.steps, args.warmup
-    ld = (P + 3) // 4 * 4 + 4 * max(0, args.ld_pad // 4)
+    gap = 4 * max(0, args.gap // 4)
+    ld = (P + 3) // 4 * 4 + 4 * max(0, args.ld_pad // 4) + gap
     ns = {"sgd": 0, "momentum": 1, "rmsprop_mom": 2}[cfg.opt]
+    # where each tensor's gradient sits in a row: packed, or with the gap before the second half of the tensors
+    # (a single tensor is cut in two for that)
+    pieces = list(zip(offs, sizes))
+    if gap and T == 1:
+        half = (P // 2) // 4 * 4
+        pieces = [(0, half), (half, P - half)]
+    goffs = [o + (gap if gap and j >= len(pieces) // 2 else 0) for j, (o, _) in enumerate(pieces)]
 
     # ---- inputs, resident in HBM before timing -------------------------------------------
     t_gen = time.perf_counter()
@@ -257,18 +317,23 @@ def main() -> int:
     wl.grad_matrix(cfg, 0, out=g_pin.numpy(), ld=ld)
     grads = g_pin.cuda()
     del g_pin
+    if gap:                                          # move the second half of every row behind the gap, NaN in between
+        cut = pieces[len(pieces) // 2][0]
+        grads[:, cut + gap:P + gap] = grads[:, cut:P].clone()
+        grads[:, cut:cut + gap] = float("nan")
     theta = torch.from_numpy(wl.theta0(cfg)).cuda()
     state = [torch.zeros(P, device="cuda") for _ in range(ns)]
     arrivals = torch.from_numpy(np.stack([wl.arrival_times(cfg, s) for s in range(Wm + 2 * K)])).cuda()
     use_ema = args.ema_decay is not None
     ema = theta.clone() if use_ema else None
-    items = [(theta[o:o + n], state[0][o:o + n] if ns > 0 else None, state[1][o:o + n] if ns > 1 else None, o, n,
+    items = [(theta[o:o + n], state[0][o:o + n] if ns > 0 else None, state[1][o:o + n] if ns > 1 else None, go, n,
               ema[o:o + n] if use_ema else None)
-             for o, n in zip(offs, sizes)]
+             for (o, n), go in zip(pieces, goffs)]
+    T = len(items)
     tensors = bs.make_tensors(items)
     hyper = bs.make_hyper(cfg.opt, cfg.lr, cfg.momentum, cfg.decay, cfg.eps, cfg.clip_norm,
                           args.ema_decay if use_ema else 0.0, args.worker_clip)
-    ws = bs.alloc_workspace(P, N, b, T, hyper)
+    ws = bs.alloc_workspace(P + gap, N, b, T, hyper)
     sel = torch.zeros(N, dtype=torch.int32, device="cuda")
     st = torch.zeros(1, dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
@@ -290,6 +355,7 @@ def main() -> int:
     e1.record(stream)
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / K
+    fused_selection = bs.bsgd_last_step_fused_selection()
     status, _ = bs.bsgd_last_status(ws)
     if status != 0:
         print(f"bench.py: step reported status {status}", file=sys.stderr)
@@ -321,6 +387,8 @@ def main() -> int:
     gbs = req / (ms_per_step * 1e-3) / 1e9
     achieved = (req / launches) / (kernel_ms * 1e-3) / 1e9
 
+    traffic = measured_traffic(cfg.name == "C2" and not use_ema and args.worker_clip <= 0 and not gap
+                               and not args.tuning and not args.ld_pad)
     out = {
         "metric": "step GB/s and % of HBM peak at P=25M N=50 b=4 (fused RMSProp); steps/sec",
         "value": round(gbs, 2),
@@ -337,17 +405,21 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: P={P} fp32 in {T} tensor(s), N={N} kept of {W} workers, {cfg.opt}"
                                + (f", clip {cfg.clip_norm}" if cfg.clip_norm > 0 else "")
                                + (f", moving average alpha={args.ema_decay}" if use_ema else "")
-                               + (f", per-worker clip {args.worker_clip}" if args.worker_clip > 0 else ""),
+                               + (f", per-worker clip {args.worker_clip}" if args.worker_clip > 0 else "")
+                               + (f", a gap of {gap} NaN columns in the middle of every row" if gap else ""),
                    "P": P, "N": N, "b": b, "T": T, "optimizer": cfg.opt, "ld": ld,
                    "required_bytes_per_step": req},
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "steps_per_s": round(1e3 / ms_per_step, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name == "C2" and not use_ema and args.worker_clip <= 0),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": "profiles/c2_reduce_update_traffic.json (static: rocprofv3 counter runs of this "
+                                       "command, not measured in this run)" if traffic is not None else None,
                      "kernel": "k_step (reduce + fused update)", "launches_per_step": launches,
                      "kernel_ms": round(kernel_ms, 5), "kernel_ms_per_step": round(kernel_ms_step, 5),
                      "algorithmic_bytes_per_launch": req // launches},
         "input_setup_s": round(gen_s, 2),
+        "selection_inside_the_step_launch": fused_selection,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

@@ -49,11 +49,34 @@ int bsgd_set_table_mode(int32_t mode);
  * each fill the chip once; a clipped step counts both of its passes). */
 int bsgd_last_launch_count(void);
 
+/* A step small enough to go out as one launch (at most 64 workers, the narrow
+ * launch shape, no per-worker clipping) does its selection inside that launch
+ * instead of in a kernel of its own; results and everything the bsgd_last_*
+ * getters report are the same either way.  bsgd_set_fused_selection(0) makes
+ * every step use the separate selection kernel (process-wide; 1 = default);
+ * bsgd_last_step_fused_selection tells whether the calling thread's last
+ * bsgd_step / bsgd_step_ex / bsgd_step_noalloc did it inside (1) or not (0). */
+int bsgd_set_fused_selection(int32_t on);
+int bsgd_last_step_fused_selection(void);
+
 /* Measurement aid, not part of the step: a plain device-to-device copy of
  * `bytes` bytes (a multiple of 16; both pointers DEVICE, 16-byte aligned,
  * not overlapping).  It reads and writes exactly `bytes` bytes of HBM, which
  * makes it the yardstick hardware traffic counters are scaled against. */
 int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
+/* Measurement aid, not part of the step: one plain streaming kernel that reads
+ * n_read buffers and writes n_write buffers of `bytes` bytes each (1 <= n_read
+ * <= 4, 0 <= n_write <= 4; all DEVICE, 16-byte aligned; `bytes` a multiple of
+ * 16; a written buffer may be one of those read).  read_ptrs / write_ptrs are
+ * HOST arrays of DEVICE pointers.  `vec` (1, 2, 4 or 8) is the number of
+ * 16-byte groups per thread, laid out like a chunk of the step's kernel.
+ * Its bandwidth is what the memory system gives a kernel with that mix of
+ * read and written streams: the yardstick the step's passes are held
+ * against (a read-only pass, the update's three read and three written
+ * streams, pass 2 of a clipped step with three read and two written). */
+int bsgd_yardstick_streams(const void* const* read_ptrs, int32_t n_read, void* const* write_ptrs, int32_t n_write,
+                           int64_t bytes, int32_t vec, void* stream);
 
 #ifdef __cplusplus
 }

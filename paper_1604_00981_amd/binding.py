@@ -98,12 +98,18 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_set_table_mode.restype = ctypes.c_int
     lib.bsgd_last_launch_count.argtypes = []
     lib.bsgd_last_launch_count.restype = ctypes.c_int
+    lib.bsgd_set_fused_selection.argtypes = [i32]
+    lib.bsgd_set_fused_selection.restype = ctypes.c_int
+    lib.bsgd_last_step_fused_selection.argtypes = []
+    lib.bsgd_last_step_fused_selection.restype = ctypes.c_int
     lib.bsgd_num_shapes.argtypes = []
     lib.bsgd_num_shapes.restype = ctypes.c_int
     lib.bsgd_get_shape.argtypes = [i32, ctypes.POINTER(i32)]
     lib.bsgd_get_shape.restype = ctypes.c_int
     lib.bsgd_calibration_copy.argtypes = [vp, vp, i64, vp]
     lib.bsgd_calibration_copy.restype = ctypes.c_int
+    lib.bsgd_yardstick_streams.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, i64, i32, vp]
+    lib.bsgd_yardstick_streams.restype = ctypes.c_int
     lib.bsgd_last_gradient_count.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.bsgd_last_gradient_count.restype = ctypes.c_int
     lib.bsgd_precombine.argtypes = [vp, i64, i64, vp, ctypes.POINTER(i32), i32, vp, i64, vp, vp, vp]
@@ -299,6 +305,14 @@ def bsgd_last_launch_count() -> int:
     return load_library().bsgd_last_launch_count()
 
 
+def bsgd_set_fused_selection(on: bool = True) -> None:
+    _check(load_library().bsgd_set_fused_selection(1 if on else 0), "bsgd_set_fused_selection")
+
+
+def bsgd_last_step_fused_selection() -> bool:
+    return bool(load_library().bsgd_last_step_fused_selection())
+
+
 def bsgd_num_shapes() -> int:
     return load_library().bsgd_num_shapes()
 
@@ -312,6 +326,14 @@ def bsgd_get_shape(i: int) -> Tuple[int, int, int, int]:
 def bsgd_calibration_copy(dst: DevPtr, src: DevPtr, nbytes: int, stream=None) -> None:
     _check(load_library().bsgd_calibration_copy(_ptr(dst, None, "dst"), _ptr(src, None, "src"), nbytes,
                                                 _stream(stream)), "bsgd_calibration_copy")
+
+
+def bsgd_yardstick_streams(reads: Sequence[DevPtr], writes: Sequence[DevPtr], nbytes: int, vec: int = 8, stream=None) -> None:
+    """Plain streaming kernel over len(reads) read and len(writes) written buffers of nbytes each (measurement aid)."""
+    rd = (ctypes.c_void_p * max(len(reads), 1))(*[_ptr(x, None, "read") for x in reads])
+    wr = (ctypes.c_void_p * max(len(writes), 1))(*[_ptr(x, None, "write") for x in writes])
+    _check(load_library().bsgd_yardstick_streams(rd, len(reads), wr, len(writes), nbytes, vec, _stream(stream)),
+           "bsgd_yardstick_streams")
 
 
 def bsgd_last_gradient_count(workspace: torch.Tensor, stream=None) -> int:

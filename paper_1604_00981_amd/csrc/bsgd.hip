@@ -50,6 +50,9 @@ struct Variant {
   StepKernel reduce[2];      // [multi]              clipped step, pass 1: mean + sum of squares
   StepKernel rowsq[2];       // [multi]              per-worker clipping: per-row sums of squares
   StepKernel apply[3][2][2]; // [mode][multi][ema]   clipped step, pass 2: gradient from the stored mean
+  // the same first passes doing the selection themselves (one-launch steps; narrow shape only, else null)
+  StepKernel rows_sel[3][2][2];
+  StepKernel reduce_sel[2];
 };
 
 template <int BS, int V, int U, int NT>
@@ -74,6 +77,19 @@ Variant make_variant() {
   v.reduce[1] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, true, true, false>);
   v.rowsq[0] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, false>);
   v.rowsq[1] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, true>);
+  if constexpr (V == 1 && NT != 0) {
+#define BSGD_FILL_SEL(dst, MODE)                                                               \
+  dst[0][0] = reinterpret_cast<StepKernel>(&k_step<MODE, R, false, true, false, true>);        \
+  dst[0][1] = reinterpret_cast<StepKernel>(&k_step<MODE, R, false, true, true, true>);         \
+  dst[1][0] = reinterpret_cast<StepKernel>(&k_step<MODE, R, true, true, false, true>);         \
+  dst[1][1] = reinterpret_cast<StepKernel>(&k_step<MODE, R, true, true, true, true>);
+    BSGD_FILL_SEL(v.rows_sel[kSgd], kSgd)
+    BSGD_FILL_SEL(v.rows_sel[kMomentum], kMomentum)
+    BSGD_FILL_SEL(v.rows_sel[kRmspropMom], kRmspropMom)
+#undef BSGD_FILL_SEL
+    v.reduce_sel[0] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, false, true, false, true>);
+    v.reduce_sel[1] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, true, true, false, true>);
+  }
   return v;
 }
 
@@ -117,6 +133,8 @@ constexpr int kApplyRoundsPerLaunch = 8;
 constexpr int kFewRows = 8;                          // up to this many kept rows a step goes out as one launch
 std::atomic<int> g_variant{-1};                      // -1: choose by problem size
 thread_local int t_last_launches = 0;                // reduce/update launches of this thread's last call
+thread_local int t_last_fused = 0;                   // 1: that call's selection ran inside its reduce/update launch
+std::atomic<int> g_fuse_select{1};                   // 0: never fuse (testing aid)
 
 // Automatic choice: the table is ordered widest chunk first; take the first
 // shape that still yields enough workgroups to fill every CU several times.
@@ -411,6 +429,15 @@ static int enqueue_select(const float* arrival_t, int32_t N, int32_t b, const bs
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 
+static int enqueue_select_job(int32_t N, const SelectJob& j, hipStream_t stream) {
+  const int W = j.W;
+  void (*fn)(const float*, int, int, SelectOpts, int*, int*, float*, int*) =
+      W <= 64 ? k_select<1, true> : W <= 128 ? k_select<2, false> : W <= 192 ? k_select<3, false> : k_select<4, false>;
+  hipLaunchKernelGGL(fn, dim3(1), dim3(64), 0, stream, j.arrival_t, (int)N, W, j.opts, j.sel_idx, j.n_kept, j.t_step,
+                     j.status);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
 int bsgd_select_first_n(const float* arrival_t, int32_t N, int32_t b, int32_t* sel_idx, float* t_step,
                         int32_t* status, void* stream) {
   if (!check_select_args(arrival_t, N, b) || sel_idx == nullptr || status == nullptr) return BSGD_ERR_ARG;
@@ -511,11 +538,18 @@ static int make_plan(const float* grads, int64_t ld, int32_t N, const bsgd_tenso
 
 // N: kept rows when the host knows the count (n_dev null); otherwise the count is read from n_dev on the device and
 // row_cap is the most it can be (N+b in the time-out mode).  Everything sized per kept row uses row_cap.
+static int enqueue_select_job(int32_t N, const SelectJob& j, hipStream_t stream);
+
+// job: the selection this update belongs to, not yet enqueued (null: sel_idx is ready, or will be by stream order).
+// A step that goes out as one launch of the narrow shape does the selection inside that launch; otherwise
+// k_select is enqueued first.
 static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,
                           int32_t row_cap, const int32_t* n_dev, const int32_t* div_dev, int32_t T,
-                          const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream) {
+                          const bsgd_hyper* hyper, void* workspace, const Plan& plan, hipStream_t stream,
+                          const SelectJob* job = nullptr) {
   t_last_launches = 0;
-  if (plan.S == 0) return BSGD_OK;
+  t_last_fused = 0;
+  if (plan.S == 0) return job != nullptr ? enqueue_select_job(N, *job, stream) : (int)BSGD_OK;
   const int mode = hyper->opt;
   const bool clip = clip_on(hyper);
   const bool wclip = worker_clip_on(hyper);
@@ -578,6 +612,21 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   const std::vector<Run> runs = chunk_runs(plan, p.base, chunk_cols, total_chunks);
   long long slots = 0;
   for (const Run& r : runs) slots += r.count;
+  // The selection inside the step's launch: one run, one launch, at most 64 workers, no per-worker clip (its
+  // norm pass needs the kept rows first).
+  const StepKernel first_pass = clip ? var.reduce[multi ? 1 : 0] : var.rows[mode][multi ? 1 : 0][ema];
+  const StepKernel first_pass_sel = clip ? var.reduce_sel[multi ? 1 : 0] : var.rows_sel[mode][multi ? 1 : 0][ema];
+  bool fuse = job != nullptr && first_pass_sel != nullptr && job->W <= 64 && !wclip && runs.size() == 1 &&
+              g_fuse_select.load(std::memory_order_relaxed) != 0;
+  if (fuse) fuse = row_cap <= kFewRows || 2 * total_chunks < 5 * round_size(first_pass_sel, var.BS, 0);
+  if (job != nullptr && !fuse) {
+    const int rc = enqueue_select_job(N, *job, stream);
+    if (rc != BSGD_OK) return rc;
+  }
+  if (fuse) {
+    p.job = *job;
+    t_last_fused = 1;
+  }
   auto launch_runs = [&](StepKernel fn, int rounds) {
     long long slot = 0;
     for (const Run& r : runs) {
@@ -596,9 +645,9 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  if (!clip) return launch_runs(var.rows[mode][multi ? 1 : 0][ema], row_rounds);
+  if (!clip) return launch_runs(fuse ? first_pass_sel : first_pass, fuse ? (1 << 20) : row_rounds);
 
-  int rc = launch_runs(var.reduce[multi ? 1 : 0], row_rounds);
+  int rc = launch_runs(fuse ? first_pass_sel : first_pass, fuse ? (1 << 20) : row_rounds);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)slots, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
@@ -639,10 +688,18 @@ static int step_common(const float* grads, int64_t ld, const float* arrival_t, i
   int* sel = reinterpret_cast<int*>(ws + kAlign);
   int32_t* status = status_out != nullptr ? status_out : &hdr->status;
   float* t_step = status_out != nullptr ? t_step_out : &hdr->t_step;
-  rc = enqueue_select(arrival_t, N, b, opts, sel, &hdr->n_kept, &hdr->n_grad, t_step, status, (hipStream_t)stream);
-  if (rc != BSGD_OK) return rc;
+  SelectJob job{};
+  job.arrival_t = arrival_t;
+  job.W = N + b;
+  job.opts = SelectOpts{nullptr, 0, INFINITY, 0, nullptr, &hdr->n_grad};
+  if (opts != nullptr)
+    job.opts = SelectOpts{opts->tags, opts->step_tag, opts->deadline, opts->n_min, opts->row_count, &hdr->n_grad};
+  job.sel_idx = sel;
+  job.n_kept = &hdr->n_kept;
+  job.t_step = t_step;
+  job.status = status;
   return enqueue_update(grads, ld, sel, status, N, all_in_time ? N + b : N, all_in_time ? &hdr->n_kept : nullptr,
-                        counted ? &hdr->n_grad : nullptr, T, hyper, workspace, plan, (hipStream_t)stream);
+                        counted ? &hdr->n_grad : nullptr, T, hyper, workspace, plan, (hipStream_t)stream, &job);
 }
 
 int bsgd_step(const float* grads, int64_t ld, const float* arrival_t, int32_t N, int32_t b,
@@ -767,6 +824,14 @@ int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontempo
 
 int bsgd_last_launch_count(void) { return t_last_launches; }
 
+int bsgd_last_step_fused_selection(void) { return t_last_fused; }
+
+int bsgd_set_fused_selection(int32_t on) {
+  if (on != 0 && on != 1) return BSGD_ERR_ARG;
+  g_fuse_select.store(on, std::memory_order_relaxed);
+  return BSGD_OK;
+}
+
 int bsgd_set_table_mode(int32_t mode) {
   if (mode != 0 && mode != 1) return BSGD_ERR_ARG;
   g_table_mode.store(mode, std::memory_order_relaxed);
@@ -790,6 +855,32 @@ int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* strea
   if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
   hipLaunchKernelGGL(k_calibration_copy, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const f4*>(src), static_cast<f4*>(dst), n16);
+  return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
+}
+
+int bsgd_yardstick_streams(const void* const* read_ptrs, int32_t n_read, void* const* write_ptrs, int32_t n_write,
+                           int64_t bytes, int32_t vec, void* stream) {
+  if (n_read < 1 || n_read > kYardMaxStreams || n_write < 0 || n_write > kYardMaxStreams || read_ptrs == nullptr ||
+      (n_write > 0 && write_ptrs == nullptr) || bytes <= 0 || (bytes & 15) != 0)
+    return BSGD_ERR_ARG;
+  YardArgs a{};
+  for (int i = 0; i < n_read; ++i) {
+    if (read_ptrs[i] == nullptr || (reinterpret_cast<uintptr_t>(read_ptrs[i]) & 15) != 0) return BSGD_ERR_ARG;
+    a.rd[i] = static_cast<const f4*>(read_ptrs[i]);
+  }
+  for (int i = 0; i < n_write; ++i) {
+    if (write_ptrs[i] == nullptr || (reinterpret_cast<uintptr_t>(write_ptrs[i]) & 15) != 0) return BSGD_ERR_ARG;
+    a.wr[i] = static_cast<f4*>(write_ptrs[i]);
+  }
+  a.n_read = n_read;
+  a.n_write = n_write;
+  a.n16 = bytes / 16;
+  void (*fn)(YardArgs) = vec == 1 ? k_yardstick<1> : vec == 2 ? k_yardstick<2> : vec == 4 ? k_yardstick<4>
+                         : vec == 8 ? k_yardstick<8> : nullptr;
+  if (fn == nullptr) return BSGD_ERR_ARG;
+  const long long grid = (a.n16 + 256LL * vec - 1) / (256LL * vec);
+  if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
+  hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, a);
   return hipGetLastError() == hipSuccess ? BSGD_OK : BSGD_ERR_HIP;
 }
 

@@ -64,36 +64,6 @@ struct WsHeader {
   int n_grad;          // how many worker gradients those rows hold: the divisor of the mean
 };
 
-struct StepParams {
-  const float* grads;        // [(N+b) x ld]
-  long long ld;
-  const int* sel_idx;        // [N] ascending
-  const int* status;         // may be null
-  int N;
-  float inv_n;
-  const int* n_dev;          // when set: the number of kept rows is read from here (deadline mode)
-  const int* div_dev;        // when set: the divisor of the mean is read from here (rows that hold several gradients)
-  const float* row_scale;    // per kept row: its own clip scale (per-worker clipping), or null
-  double* row_partials;      // [chunk][n_stride]: per chunk and kept row, sum of squares (per-worker clipping)
-  int n_stride;              // rows per chunk in row_partials
-  float worker_clip;         // c of the per-worker clip
-  float lr, mu, rho, one_minus_rho, eps;
-  float alpha, one_minus_alpha;   // decay of the moving average of theta
-  // clipped steps
-  float* gbar;               // mean gradient, laid out like one gradient row
-  double* partials;          // one sum of squares per workgroup
-  const WsHeader* header;    // clip_scale is read from here by k_apply
-  // segments (tensors and gaps) in gradient-row column order
-  Segment single;            // the one tensor when there is exactly one
-  const Segment* table;      // [S] in the workspace; null: the launch carries its part of the table as its second argument
-  const unsigned* starts;    // [S+1] first column of each segment, then the end of the last one
-  int S;                     // segments in the table this launch sees
-  long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
-  long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
-  int chunk_base;            // chunk id of workgroup 0 of this launch
-  int slot_base;             // index of workgroup 0's slot in partials / row_partials (chunks that hold no tensor
-                             // are not launched and have no slot)
-};
 
 // ---------------------------------------------------------------------------
 // Arrival-order selection
@@ -132,12 +102,23 @@ struct SelectOpts {
 // where it takes the same 4.1 us inside a step as the LDS form); otherwise
 // they are put in LDS and read back as broadcasts (faster from two slots per
 // lane on: W = 106: 4.4 against 4.6 us, W = 256: 1.8 us less per launch).
+// What a wavefront knows once it has ranked the arrival times (all wave-uniform).
+struct Selected {
+  int status;                    // BSGD_OK, BSGD_ERR_TOO_FEW, or BSGD_ERR_ARG for a kept row that holds no gradient
+  int n_kept;                    // rows kept (0 when too few)
+  int n_grad;                    // worker gradients those rows hold
+  unsigned long long mask;       // bit w: worker w is kept (workers 0..63; the whole set when W <= 64)
+};
+
+// The selection, run by one whole wavefront (any wavefront of a workgroup:
+// `lane` is the lane index).  Outputs go through the pointers that are not
+// null; the result is also returned, so a kernel can run it for itself.
 template <int R, bool DPP>
-__global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival_t, int N, int W, SelectOpts o,
+__device__ __forceinline__ Selected select_wave(const float* __restrict__ arrival_t, int N, int W, SelectOpts o,
                                                 int* __restrict__ sel_idx, int* __restrict__ n_kept,
                                                 float* __restrict__ t_step, int* __restrict__ status) {
-  __shared__ unsigned long long keys[64 * R];
-  const int lane = threadIdx.x;
+  __shared__ unsigned long long keys[DPP ? 1 : 64 * R];
+  const int lane = threadIdx.x & 63;
   unsigned long long key[R];
   float tval[R];
   int eligible = 0;
@@ -203,13 +184,15 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
   }
 
   int base = 0;
+  unsigned long long first_mask = 0;
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int w = lane + 64 * r;
     const bool keep = (w < W) && (rank[r] < K);
     const unsigned long long mask = __ballot(keep);
+    if (r == 0) first_mask = mask;
     const int pos = base + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
-    if (keep) sel_idx[pos] = w;
+    if (keep && sel_idx) sel_idx[pos] = w;
     base += __popcll(mask);
     if ((w < W) && rank[r] == K - 1 && t_step) *t_step = tval[r];   // the last kept arrival: how long the step waited
   }
@@ -229,12 +212,73 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
     held += __shfl_xor(held, off, 64);
     bad |= __shfl_xor(bad, off, 64);
   }
+  Selected out;
+  out.status = too_few ? -2 : (bad ? -1 : 0);
+  out.n_kept = too_few ? 0 : K;
+  out.n_grad = held;
+  out.mask = first_mask;
   if (lane == 0) {
-    *status = too_few ? -2 : (bad ? -1 : 0);
-    if (n_kept) *n_kept = too_few ? 0 : K;
+    if (status) *status = out.status;
+    if (n_kept) *n_kept = out.n_kept;
     if (o.n_grad) *o.n_grad = held;
   }
+  return out;
 }
+
+template <int R, bool DPP>
+__global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival_t, int N, int W, SelectOpts o,
+                                                int* __restrict__ sel_idx, int* __restrict__ n_kept,
+                                                float* __restrict__ t_step, int* __restrict__ status) {
+  select_wave<R, DPP>(arrival_t, N, W, o, sel_idx, n_kept, t_step, status);
+}
+
+// The selection as part of a step that goes out as ONE launch (small
+// problems, where a launch of its own for k_select is a third of the step):
+// every wavefront of the step's kernel ranks the W <= 64 arrival times itself
+// (DPP rotates only: no LDS, no barrier, no other wavefront to wait for) and
+// takes the kept rows from the resulting 64-bit mask; the first wavefront of
+// the launch also publishes what k_select would have written.
+struct SelectJob {
+  const float* arrival_t;
+  int W;
+  SelectOpts opts;
+  int* sel_idx;              // outputs, as k_select's
+  int* n_kept;
+  float* t_step;
+  int* status;
+};
+
+struct StepParams {
+  const float* grads;        // [(N+b) x ld]
+  long long ld;
+  const int* sel_idx;        // [N] ascending
+  const int* status;         // may be null
+  int N;
+  float inv_n;
+  const int* n_dev;          // when set: the number of kept rows is read from here (deadline mode)
+  const int* div_dev;        // when set: the divisor of the mean is read from here (rows that hold several gradients)
+  const float* row_scale;    // per kept row: its own clip scale (per-worker clipping), or null
+  double* row_partials;      // [chunk][n_stride]: per chunk and kept row, sum of squares (per-worker clipping)
+  int n_stride;              // rows per chunk in row_partials
+  float worker_clip;         // c of the per-worker clip
+  float lr, mu, rho, one_minus_rho, eps;
+  float alpha, one_minus_alpha;   // decay of the moving average of theta
+  // clipped steps
+  float* gbar;               // mean gradient, laid out like one gradient row
+  double* partials;          // one sum of squares per workgroup
+  const WsHeader* header;    // clip_scale is read from here by k_apply
+  // segments (tensors and gaps) in gradient-row column order
+  Segment single;            // the one tensor when there is exactly one
+  const Segment* table;      // [S] in the workspace; null: the launch carries its part of the table as its second argument
+  const unsigned* starts;    // [S+1] first column of each segment, then the end of the last one
+  int S;                     // segments in the table this launch sees
+  long long col_lo, col_hi;  // columns covered by tensors: [col_lo, col_hi)
+  long long base;            // col_lo rounded down to a multiple of 4: column of chunk 0
+  int chunk_base;            // chunk id of workgroup 0 of this launch
+  int slot_base;             // index of workgroup 0's slot in partials / row_partials (chunks that hold no tensor
+                             // are not launched and have no slot)
+  SelectJob job;             // kernels with SELECT: the selection is theirs to do (sel_idx, status, n_dev, div_dev unused)
+};
 
 // ---------------------------------------------------------------------------
 // Tensor table
@@ -322,15 +366,23 @@ __device__ __forceinline__ void fma4(f4& acc, float scale, const f4& r) {
 // steady pipelines of 2..8 loads per thread are 0..5 % slower; left to
 // itself the compiler picks one or the other depending on the register
 // pressure of the rest of the kernel.
-template <int V, int B, bool NT>
+// MASK: the kept rows are the set bits of `mask`, taken from the lowest up
+// (the same ascending order as the list) and cleared as they are used.
+template <int V, int B, bool NT, bool MASK>
 __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
-                                         long long colbase, const int* __restrict__ sel_idx,
+                                         long long colbase, const int* __restrict__ sel_idx, unsigned long long& mask,
                                          const float* __restrict__ row_scale, int j, const unsigned (&toff)[V]) {
   const char* rowbase[B];
   float sc[B];
 #pragma unroll
   for (int u = 0; u < B; ++u) {
-    const long long k = sel_idx[j + u];
+    long long k;
+    if constexpr (MASK) {
+      k = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(mask));   // the mask is the same in every lane
+      mask &= mask - 1;
+    } else {
+      k = sel_idx[j + u];
+    }
     sc[u] = row_scale != nullptr ? row_scale[j + u] : 1.0f;   // per-worker clip scale (wave-uniform)
     rowbase[u] = reinterpret_cast<const char*>(grads + k * ld + colbase);
   }
@@ -371,16 +423,16 @@ __device__ __forceinline__ void add_rows(f4 (&acc)[V], const float* __restrict__
 }
 
 // All kept rows, in batches of U (then 8, 4, 2, 1 for what is left).
-template <int V, int U, bool NT>
+template <int V, int U, bool NT, bool MASK = false>
 __device__ __forceinline__ void sum_rows(f4 (&acc)[V], const float* __restrict__ grads, long long ld,
-                                         long long colbase, const int* __restrict__ sel_idx,
+                                         long long colbase, const int* __restrict__ sel_idx, unsigned long long mask,
                                          const float* __restrict__ row_scale, int N, const unsigned (&toff)[V]) {
   int j = 0;
-  for (; j + U <= N; j += U) add_rows<V, U, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff);
-  if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 8; } }
-  if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 4; } }
-  if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 2; } }
-  if constexpr (U > 1) { if ((N - j) & 1) { add_rows<V, 1, NT>(acc, grads, ld, colbase, sel_idx, row_scale, j, toff); j += 1; } }
+  for (; j + U <= N; j += U) add_rows<V, U, NT, MASK>(acc, grads, ld, colbase, sel_idx, mask, row_scale, j, toff);
+  if constexpr (U > 8) { if ((N - j) & 8) { add_rows<V, 8, NT, MASK>(acc, grads, ld, colbase, sel_idx, mask, row_scale, j, toff); j += 8; } }
+  if constexpr (U > 4) { if ((N - j) & 4) { add_rows<V, 4, NT, MASK>(acc, grads, ld, colbase, sel_idx, mask, row_scale, j, toff); j += 4; } }
+  if constexpr (U > 2) { if ((N - j) & 2) { add_rows<V, 2, NT, MASK>(acc, grads, ld, colbase, sel_idx, mask, row_scale, j, toff); j += 2; } }
+  if constexpr (U > 1) { if ((N - j) & 1) { add_rows<V, 1, NT, MASK>(acc, grads, ld, colbase, sel_idx, mask, row_scale, j, toff); j += 1; } }
 }
 
 // The library is compiled with floating-point contraction off and spells its
@@ -553,18 +605,35 @@ __device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsig
 // (nearly all of them) takes the uniform path with wave-uniform pointers and
 // float4 accesses (4-byte aligned only, since a tensor may start anywhere in
 // the row); a chunk holding a tensor boundary looks segments up per lane.
-template <int MODE, class S, bool MULTI, bool SRC_ROWS, bool EMA>
+// SELECT (with SRC_ROWS): the launch is the whole step and does the selection itself, see SelectJob.
+template <int MODE, class S, bool MULTI, bool SRC_ROWS, bool EMA, bool SELECT = false>
 __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
+  static_assert(!SELECT || SRC_ROWS, "only a pass over the gradient rows can do the selection");
   constexpr int BS = S::BS, V = S::V, U = S::U;
   constexpr bool NT = S::NT;
   constexpr long long CH = 4LL * BS * V;               // columns per chunk
   extern __shared__ unsigned starts_lds[];             // MULTI: starts[S+1]
   __shared__ float red_lds[BS / 64];
 
-  if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
-  const int n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
-  const float inv_n = p.div_dev != nullptr ? 1.0f / (float)*p.div_dev
-                                           : (p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n);
+  int n_rows;
+  float inv_n;
+  unsigned long long row_mask = 0;
+  if constexpr (SELECT) {
+    const bool publish = blockIdx.x == 0 && threadIdx.x < 64;   // one wavefront of the (single) launch writes the outputs
+    SelectOpts o = p.job.opts;
+    if (!publish) o.n_grad = nullptr;
+    const Selected sel = select_wave<1, true>(p.job.arrival_t, p.N, p.job.W, o, publish ? p.job.sel_idx : nullptr,
+                                              publish ? p.job.n_kept : nullptr, publish ? p.job.t_step : nullptr,
+                                              publish ? p.job.status : nullptr);
+    if (sel.status != 0) return;                      // too few arrivals: touch nothing
+    row_mask = sel.mask;
+    n_rows = sel.n_kept;
+    inv_n = o.row_count != nullptr ? 1.0f / (float)sel.n_grad : (o.n_min > 0 ? 1.0f / (float)n_rows : p.inv_n);
+  } else {
+    if (p.status != nullptr && *p.status != 0) return;  // too few arrivals: touch nothing
+    n_rows = p.n_dev != nullptr ? *p.n_dev : p.N;
+    inv_n = p.div_dev != nullptr ? 1.0f / (float)*p.div_dev : (p.n_dev != nullptr ? 1.0f / (float)n_rows : p.inv_n);
+  }
 
   const Segment* table;
   const unsigned* starts;
@@ -633,7 +702,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
     if constexpr (SRC_ROWS) {
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] = f4{0.f, 0.f, 0.f, 0.f};
-      sum_rows<V, U, NT>(g, p.grads, p.ld, c0, p.sel_idx, p.row_scale, n_rows, toff);
+      sum_rows<V, U, NT, SELECT>(g, p.grads, p.ld, c0, p.sel_idx, row_mask, p.row_scale, n_rows, toff);
 #pragma unroll
       for (int v = 0; v < V; ++v) g[v] *= inv_n;
     } else {
@@ -1151,6 +1220,55 @@ __global__ __launch_bounds__(kMeanBlock) void k_mean_kth(const double* __restric
 __global__ __launch_bounds__(256) void k_calibration_copy(const f4* __restrict__ src, f4* __restrict__ dst, long long n16) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i < n16) dst[i] = src[i];
+}
+
+// Plain streaming kernel with a chosen mix of streams: reads n_read buffers,
+// writes n_write buffers (a written buffer may be one of those read: in-place,
+// like theta and state), V 16-byte groups per thread laid out like a k_step
+// chunk, streaming hints on every access.  It does nothing else, so its
+// bandwidth is what the memory system gives a kernel with that mix: the
+// yardstick the step's passes are held against.
+constexpr int kYardMaxStreams = 4;
+struct YardArgs {
+  const f4* rd[kYardMaxStreams];
+  f4* wr[kYardMaxStreams];
+  int n_read, n_write;
+  long long n16;             // 16-byte groups per stream
+};
+
+template <int V>
+__global__ __launch_bounds__(256) void k_yardstick(YardArgs a) {
+  const long long base = (long long)blockIdx.x * (256LL * V) + threadIdx.x;
+  f4 x[kYardMaxStreams][V];
+#pragma unroll
+  for (int s = 0; s < kYardMaxStreams; ++s)
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      x[s][v] = f4{0.f, 0.f, 0.f, 0.f};
+      const long long i = base + v * 256LL;
+      if (s < a.n_read && i < a.n16) x[s][v] = __builtin_nontemporal_load(a.rd[s] + i);
+    }
+  f4 y[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    y[v] = x[0][v];
+#pragma unroll
+    for (int s = 1; s < kYardMaxStreams; ++s) y[v] = y[v] * 0.5f + x[s][v];
+  }
+  if (a.n_write == 0) {
+    // read-only mix: keep the loads alive without writing (the sum of finite inputs is never NaN-equal to this pattern)
+    float t = 0.f;
+#pragma unroll
+    for (int v = 0; v < V; ++v) t += y[v].x + y[v].y + y[v].z + y[v].w;
+    if (__float_as_uint(t) == 0x7fc12345u && a.wr[0] != nullptr) a.wr[0][0] = y[0];
+  }
+#pragma unroll
+  for (int s = 0; s < kYardMaxStreams; ++s)
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const long long i = base + v * 256LL;
+      if (s < a.n_write && i < a.n16) __builtin_nontemporal_store(y[v] + (float)s, a.wr[s] + i);
+    }
 }
 
 }  // namespace bsgd

@@ -591,6 +591,75 @@ def test_every_compiled_launch_shape_every_instantiation_against_the_oracle(kind
                 assert np.array_equal(a[k], bb[k]), k   # rows are added in the same order whatever the shape
 
 
+_FUSED_KINDS = {
+    # kind: (N, b, layout, optimizer, hyper-parameters, moving average, selection options)
+    "sgd_single": (4, 1, [(0, 70_001)], "sgd", {}, None, None),
+    "rmsprop_multi_ema": (9, 3, [(3, 9001), (9004, 17), (9100, 20000)], "rmsprop_mom", {}, 0.9, None),
+    "momentum_multi_clip": (9, 3, [(3, 9001), (9004, 17), (9100, 20000)], "momentum", dict(clip_norm=0.003), None, None),
+    "sgd_clip_ema_64_workers": (60, 4, [(1, 30_011)], "sgd", dict(clip_norm=0.001), 0.5, None),
+    "momentum_deadline_tags": (7, 4, [(0, 12_345), (12_345, 678)], "momentum", {}, None, "deadline+tags"),
+}
+
+
+@pytest.mark.parametrize("kind", sorted(_FUSED_KINDS))
+def test_selection_inside_the_step_launch_equals_the_separate_kernel(kind):
+    # A small step goes out as one launch that ranks the arrival times itself (every wavefront, from a 64-bit mask of
+    # the kept rows); with that switched off the same step runs k_select first.  Same bits, same recorded outputs;
+    # both against the oracle.  Then too few arrivals: nothing may be touched either way.
+    import paper_1604_00981_amd as bs
+    N, b, layout, opt, hyper, ema, sel_mode = _FUSED_KINDS[kind]
+    out = {}
+    try:
+        for fused in (True, False):
+            bs.bsgd_set_fused_selection(fused)
+            c = Case(N, b, layout, opt, seed=95, theta_shift=1, hyper=hyper, ema=ema)
+            rec = []
+            for step in range(3):
+                g, t = c.draw()
+                opts = None
+                if sel_mode is not None:
+                    opts = dict(deadline=float(np.sort(t)[N + step]), n_min=3, step_tag=step,
+                                tags=np.where(c.r.random(c.W) < 0.2, step - 1, step).astype(np.int32))
+                assert c.both(g, t, opts) == 0
+                assert bs.bsgd_last_step_fused_selection() == fused
+                assert bs.bsgd_last_launch_count() == (2 if "clip_norm" in hyper else 1)
+                nk = bs.bsgd_last_kept_count(c.ws)
+                rec.append((nk, bs.bsgd_last_selection(c.ws, nk), bs.bsgd_last_status(c.ws), bs.bsgd_last_gradient_count(c.ws)))
+            c.compare()
+            before = c.gpu_arrays()
+            g, t = c.draw()
+            t[:b + 1] = np.inf                                   # one arrival short
+            assert c.both(g, t, None if sel_mode is None else dict(n_min=N)) == bs.BSGD_ERR_TOO_FEW
+            assert bs.bsgd_last_step_fused_selection() == fused
+            assert bs.bsgd_last_kept_count(c.ws) == 0
+            after = c.gpu_arrays()
+            for k in before:
+                assert np.array_equal(before[k], after[k]), k
+            out[fused] = (after, rec)
+    finally:
+        bs.bsgd_set_fused_selection(True)
+    assert out[True][1] == out[False][1]
+    for k in out[True][0]:
+        assert np.array_equal(out[True][0][k], out[False][0][k]), k
+
+
+def test_selection_stays_a_kernel_of_its_own_where_the_step_is_not_one_small_launch():
+    import paper_1604_00981_amd as bs
+    # more than 64 workers
+    c = Case(70, 5, [(0, 3001)], "sgd", seed=96)
+    c.both(*c.draw())
+    assert not bs.bsgd_last_step_fused_selection()
+    # per-worker clipping needs the kept rows before its norm pass
+    c = Case(5, 2, [(0, 3001)], "sgd", seed=97, hyper=dict(worker_clip_norm=0.5))
+    c.both(*c.draw())
+    assert not bs.bsgd_last_step_fused_selection()
+    # several launches (many rows, more than 2.5 rounds of narrow chunks)
+    c = Case(12, 2, [(0, 1_500_000)], "sgd", seed=98)
+    c.both(*c.draw())
+    assert not bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() >= 2
+    c.compare()
+
+
 def _irregular_layout(total, count, seed, crowded=0):
     """`count` tensors of irregular sizes packed back to back over about `total` columns; with `crowded`, that many
     tiny tensors come first (more than one launch can carry as an argument)."""
