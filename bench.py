@@ -139,7 +139,7 @@ def yardstick_main(args, bs) -> int:
 
     P2, P5 = 25_000_000, 134_217_728
     rows = []
-    for vec in (8, 1):
+    for vec in (8, 4, 2, 1):
         rows.append(run("read only, one 5.4 GB buffer (the kept rows of C2)", 54 * P2, 1, 0, vec))
         rows.append(run("update of C2: theta, ms, m read and written in place", P2, 3, 3, vec))
         rows.append(run("pass 2 of a clipped step at C5's size: stored mean, theta, v read; theta, v written", P5, 3, 2, vec))

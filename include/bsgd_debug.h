@@ -71,6 +71,8 @@ int bsgd_calibration_copy(void* dst, const void* src, int64_t bytes, void* strea
  * 16; a written buffer may be one of those read).  read_ptrs / write_ptrs are
  * HOST arrays of DEVICE pointers.  `vec` (1, 2, 4 or 8) is the number of
  * 16-byte groups per thread, laid out like a chunk of the step's kernel.
+ * Compiled mixes (n_read, n_write): (1,0) (3,3) (3,2) (2,2) (2,1) (1,1);
+ * any other returns BSGD_ERR_ARG.
  * Its bandwidth is what the memory system gives a kernel with that mix of
  * read and written streams: the yardstick the step's passes are held
  * against (a read-only pass, the update's three read and three written

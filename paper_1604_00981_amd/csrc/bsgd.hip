@@ -875,9 +875,15 @@ int bsgd_yardstick_streams(const void* const* read_ptrs, int32_t n_read, void* c
   a.n_read = n_read;
   a.n_write = n_write;
   a.n16 = bytes / 16;
-  void (*fn)(YardArgs) = vec == 1 ? k_yardstick<1> : vec == 2 ? k_yardstick<2> : vec == 4 ? k_yardstick<4>
-                         : vec == 8 ? k_yardstick<8> : nullptr;
-  if (fn == nullptr) return BSGD_ERR_ARG;
+  // the mixes of the step's passes: read only; update of theta/ms/m; pass 2 of a clipped step; pre-combine; copy
+  void (*fn)(YardArgs) = nullptr;
+#define BSGD_YARD(R, W)                                                                           \
+  if (n_read == R && n_write == W)                                                                \
+    fn = vec == 1 ? k_yardstick<1, R, W> : vec == 2 ? k_yardstick<2, R, W>                        \
+         : vec == 4 ? k_yardstick<4, R, W> : vec == 8 ? k_yardstick<8, R, W> : nullptr;
+  BSGD_YARD(1, 0) BSGD_YARD(3, 3) BSGD_YARD(3, 2) BSGD_YARD(2, 2) BSGD_YARD(2, 1) BSGD_YARD(1, 1)
+#undef BSGD_YARD
+  if (fn == nullptr) return BSGD_ERR_ARG;               // a mix or width that is not compiled in
   const long long grid = (a.n16 + 256LL * vec - 1) / (256LL * vec);
   if (grid > 0x7fffffffLL) return BSGD_ERR_ARG;
   hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, a);
