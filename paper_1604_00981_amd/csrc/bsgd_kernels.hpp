@@ -102,6 +102,8 @@ struct SelectOpts {
 // where it takes the same 4.1 us inside a step as the LDS form); otherwise
 // they are put in LDS and read back as broadcasts (faster from two slots per
 // lane on: W = 106: 4.4 against 4.6 us, W = 256: 1.8 us less per launch).
+constexpr int kFewWorkers = 24;                      // up to here the keys are broadcast one by one (see select_wave)
+
 // What a wavefront knows once it has ranked the arrival times (all wave-uniform).
 struct Selected {
   int status;                    // BSGD_OK, BSGD_ERR_TOO_FEW, or BSGD_ERR_ARG for a kept row that holds no gradient
@@ -148,7 +150,17 @@ __device__ __forceinline__ Selected select_wave(const float* __restrict__ arriva
   int rank[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) rank[r] = 0;
-  if constexpr (DPP) {
+  if (DPP && R == 1 && W <= kFewWorkers) {
+    // A handful of workers: every real key is broadcast in turn (lane j's
+    // key through a scalar register), W steps instead of 63.  The key's own
+    // lane compares it with itself, which counts nothing.
+    const int lo = (int)(unsigned)key[0], hi = (int)(unsigned)(key[0] >> 32);
+    for (int j = 0; j < W; ++j) {
+      const unsigned long long kj = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi, j) << 32) |
+                                    (unsigned)__builtin_amdgcn_readlane(lo, j);
+      rank[0] += (kj < key[0]) ? 1 : 0;
+    }
+  } else if constexpr (DPP) {
     // The keys travel round the wavefront one lane at a time (DPP wave rotate):
     // after 63 steps every lane has seen every other lane's keys.  Padding
     // slots hold the largest key and are never counted.
@@ -505,8 +517,8 @@ __device__ __forceinline__ double block_sum(float x, float* lds) {
 // that came out of an integer, or was read from a table in memory, is
 // "generic" to the compiler and is accessed with the generic instructions
 // and a 64-bit address register pair per access; a wave-uniform global
-// pointer plus a 32-bit lane offset needs neither (RMSProp-mom, one tensor:
-// 152 registers instead of 178).  Every theta/state pointer handed to the
+// pointer plus a 32-bit lane offset needs neither (26 vector registers fewer
+// in the RMSProp-mom kernel when this was introduced).  Every theta/state pointer handed to the
 // library is device memory, so the cast is safe.
 typedef __attribute__((address_space(1))) char gbyte;
 typedef __attribute__((address_space(1))) float gfloat;
