@@ -31,7 +31,10 @@ or NaN means the message never arrives, and fewer than N arrivals means no
 update; momentum is v <- mu v + G, theta <- theta - gamma v; RMSProp with
 momentum is ms <- rho ms + (1-rho) G^2, m <- mu m + gamma G / sqrt(ms + eps),
 theta <- theta - m; clipping acts on the aggregated mean gradient with
-scale min(1, c/||G||); a machine's combined message leaves when its last
+scale min(1, c/||G||); with time-outs in place of backup workers (Sec. 6)
+the parameter side listens until the deadline and keeps every current-step
+message that came in by then, however many of the N+b that is, and the mean
+divides by that number; a machine's combined message leaves when its last
 worker is done, N then counts messages, and the mean still divides by the
 number of worker gradients the kept messages hold.
 
@@ -41,6 +44,9 @@ collect loop, the plain mean for b=0, exact rational arithmetic on tiny
 inputs, NaN-poisoned dropped rows, joint permutation of workers, closed-form
 SGD / momentum / RMSProp trajectories for constant gradients, numpy's norm
 for clipping, closed forms and exact rational replay for the moving average;
+for the time-out variant: the message-queue replay listening until the
+deadline, with fewer and with more than N messages in time, a hand case, the
+divisor of a whole step, exact replay together with per-worker clipping;
 for pre-combined messages: groups of one are the identity, b=0 equals the
 plain mean over all workers, uniform groups equal the step on the workers
 themselves with their machine's time, exact rational replay.  No function

@@ -100,3 +100,38 @@ def test_too_few_arrivals_and_limits():
     hy0 = bs.make_hyper("sgd", 0.1)
     assert bs.bsgd_workspace_bytes(P, 4, 1, 1, hy0) <= bs.BSGD_STATIC_SCRATCH_BYTES
     assert lib.bsgd_step_noalloc(A, P, A, 4, 1, tz, 1, ctypes.byref(hy0), None, None, None) == bs.BSGD_ERR_ARG
+
+
+def test_recorded_into_a_graph_and_replayed():
+    # what the entry point is for: a capture may not allocate, and this call does not.  The first call on the device
+    # (which looks the scratch array's address up) has happened above or happens here, before the capture.
+    import torch
+    import paper_1604_00981_amd as bs
+    lib = bs.load_library()
+    layout = [(3, 9001), (9004, 17), (9100, 20000)]
+    ref, dut = _pair(7, 3, layout, "momentum", 84, hyper=dict(clip_norm=0.01), ema=0.99)
+    warm = Case(7, 3, layout, "momentum", seed=85, theta_shift=1, hyper=dict(clip_norm=0.01), ema=0.99)
+    g, t = warm.draw()
+    assert _noalloc_step(warm, g, t)[0] == 0
+    g_dev = torch.zeros((dut.W, dut.ld), device="cuda")
+    t_dev = torch.zeros(dut.W, device="cuda")
+    st = torch.full((1,), -99, dtype=torch.int32, device="cuda")
+    ts = torch.zeros(1, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = lib.bsgd_step_noalloc(g_dev.data_ptr(), dut.ld, t_dev.data_ptr(), dut.N, dut.b, dut.tensors,
+                                   len(dut.tensors), ctypes.byref(dut.hyper), st.data_ptr(), ts.data_ptr(), stream)
+    assert rc == bs.BSGD_OK
+    for rep in range(3):
+        g, t = ref.draw()
+        g_dev.copy_(torch.from_numpy(g))
+        t_dev.copy_(torch.from_numpy(t))
+        graph.replay()
+        assert ref.both(g, t) == 0                      # eager bsgd_step between the replays, checked against the oracle
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0 and np.float32(ts.item()) == np.float32(ref.bs.bsgd_last_status(ref.ws)[1])
+        ga, gb = ref.gpu_arrays(), dut.gpu_arrays()
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), (rep, k)
+    ref.compare()
