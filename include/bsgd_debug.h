@@ -15,6 +15,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "bsgd.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -48,6 +50,19 @@ int bsgd_set_table_mode(int32_t mode);
  * bsgd_step / bsgd_reduce_update enqueued (a step is cut into launches that
  * each fill the chip once; a clipped step counts both of its passes). */
 int bsgd_last_launch_count(void);
+
+/* Host logic made visible for testing, nothing is enqueued: the runs of chunks
+ * a call with these tensors launches when a chunk is chunk_cols columns wide
+ * (a multiple of 4).  Chunk c covers columns [base + c*chunk_cols, base +
+ * (c+1)*chunk_cols) with base = the first tensor column rounded down to a
+ * multiple of 4.  Chunks outside every run hold no tensor column and are
+ * neither launched nor read; inside a run, gaps of up to 64 chunks are
+ * tolerated.  tensors: HOST array as for bsgd_step (pointers only checked for
+ * being non-NULL and 4-byte aligned, never dereferenced).  first / count: HOST
+ * out int64[capacity]; n_runs: HOST out.  BSGD_ERR_ARG for bad tensors or
+ * when there are more runs than `capacity`. */
+int bsgd_debug_chunk_runs(const bsgd_tensor* tensors, int32_t T, int64_t chunk_cols, int64_t* first, int64_t* count,
+                          int32_t capacity, int32_t* n_runs);
 
 /* A step small enough to go out as one launch (at most 64 workers, the narrow
  * launch shape, no per-worker clipping) does its selection inside that launch

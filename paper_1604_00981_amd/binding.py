@@ -98,6 +98,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.bsgd_set_table_mode.restype = ctypes.c_int
     lib.bsgd_last_launch_count.argtypes = []
     lib.bsgd_last_launch_count.restype = ctypes.c_int
+    lib.bsgd_debug_chunk_runs.argtypes = [ctypes.POINTER(bsgd_tensor), i32, i64, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                          i32, ctypes.POINTER(i32)]
+    lib.bsgd_debug_chunk_runs.restype = ctypes.c_int
     lib.bsgd_set_fused_selection.argtypes = [i32]
     lib.bsgd_set_fused_selection.restype = ctypes.c_int
     lib.bsgd_last_step_fused_selection.argtypes = []
@@ -303,6 +306,16 @@ def bsgd_set_tuning(block: int = -1, vec: int = -1, unroll: int = -1, nontempora
 
 def bsgd_last_launch_count() -> int:
     return load_library().bsgd_last_launch_count()
+
+
+def bsgd_debug_chunk_runs(tensors, chunk_cols: int, capacity: int = 8192) -> List[Tuple[int, int]]:
+    """(first chunk, chunk count) of every run of chunks a call with these tensors launches (host logic only)."""
+    first = (ctypes.c_int64 * capacity)()
+    count = (ctypes.c_int64 * capacity)()
+    n = ctypes.c_int32(0)
+    _check(load_library().bsgd_debug_chunk_runs(tensors, len(tensors), chunk_cols, first, count, capacity, ctypes.byref(n)),
+           "bsgd_debug_chunk_runs")
+    return [(int(first[i]), int(count[i])) for i in range(n.value)]
 
 
 def bsgd_set_fused_selection(on: bool = True) -> None:

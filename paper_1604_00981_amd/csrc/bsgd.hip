@@ -822,6 +822,32 @@ int bsgd_set_tuning(int32_t block, int32_t vec, int32_t unroll, int32_t nontempo
   return BSGD_ERR_ARG;
 }
 
+int bsgd_debug_chunk_runs(const bsgd_tensor* tensors, int32_t T, int64_t chunk_cols, int64_t* first, int64_t* count,
+                          int32_t capacity, int32_t* n_runs) {
+  if (tensors == nullptr || first == nullptr || count == nullptr || n_runs == nullptr || capacity < 1 ||
+      chunk_cols < 4 || (chunk_cols & 3) != 0)
+    return BSGD_ERR_ARG;
+  // host arithmetic only: the pointers below are never dereferenced
+  bsgd_hyper hy{};
+  hy.opt = BSGD_SGD;
+  Plan plan;
+  const int rc = make_plan(reinterpret_cast<const float*>(uintptr_t(16)), (int64_t)0x7ffffffffffffffcLL, 1, tensors, T, &hy,
+                           reinterpret_cast<const void*>(uintptr_t(256)), ~(size_t)0, &plan);
+  if (rc != BSGD_OK) return rc;
+  *n_runs = 0;
+  if (plan.S == 0) return BSGD_OK;
+  const long long base = plan.col_lo & ~3LL;
+  const long long cols = ((plan.col_hi + 3) & ~3LL) - base;
+  const std::vector<Run> runs = chunk_runs(plan, base, chunk_cols, (cols + chunk_cols - 1) / chunk_cols);
+  if ((long long)runs.size() > capacity) return BSGD_ERR_ARG;
+  for (size_t i = 0; i < runs.size(); ++i) {
+    first[i] = runs[i].first;
+    count[i] = runs[i].count;
+  }
+  *n_runs = (int32_t)runs.size();
+  return BSGD_OK;
+}
+
 int bsgd_last_launch_count(void) { return t_last_launches; }
 
 int bsgd_last_step_fused_selection(void) { return t_last_fused; }
