@@ -130,7 +130,6 @@ WsLayout layout(long long span, int T, bool clip, bool worker_clip) {
 }
 
 constexpr int kApplyRoundsPerLaunch = 8;
-constexpr int kFewRows = 8;                          // up to this many kept rows a step goes out as one launch
 std::atomic<int> g_variant{-1};                      // -1: choose by problem size
 thread_local int t_last_launches = 0;                // reduce/update launches of this thread's last call
 thread_local int t_last_fused = 0;                   // 1: that call's selection ran inside its reduce/update launch
@@ -329,15 +328,33 @@ void segment_window(const Plan& plan, long long lo, long long hi, int* j0, int* 
 // table goes through the workspace instead (written once per call).
 // The chunks are first_chunk .. first_chunk+chunks-1 of the call's column
 // space; their slots in the per-chunk partial-sum arrays start at first_slot.
+// A pass goes out as ONE launch when it is small (under 2.5 rounds of chunks, or everything resident at once:
+// launch boundaries then cost more than they bring), or when a round of it moves so little that a boundary costs
+// more than letting workgroups drift (few kept rows, narrow chunks).  Measured with RMSProp-mom: wide chunks at
+// P = 25 M, N = 8 (235 MB per round): one launch +1 %, N = 16 (369 MB): rounds +1..7 %; narrow chunks at
+// P = 1.3-1.8 M (47-117 MB per round): one launch +4..8 % (N = 50), +25 % (N = 16).  Cutting a pass of 1.1-2
+// rounds into two or three launches was measured too: -1.3..+0.5 % (P = 4.5-8 M, N = 50), so it stays whole.
+constexpr double kLightRoundBytes = 250e6;
+
+bool one_launch(StepKernel fn, int block, size_t lds, long long chunks, double bytes_per_chunk) {
+  const long long round = round_size(fn, block, lds);
+  const long long resident = (long long)workgroups_per_cu(fn, block) * compute_units();
+  return chunks <= resident || 2 * chunks < 5 * round || bytes_per_chunk * (double)round < kLightRoundBytes;
+}
+
+// bytes_per_chunk: what the pass reads and writes per chunk (decides between one launch and rounds); 0 with
+// rounds_per_launch > 1 for a pass that has its own launch length.
 int launch(StepKernel fn, int block, long long first_chunk, long long first_slot, long long chunks,
-           long long chunk_cols, hipStream_t stream, StepParams& p, TableCtx* tc, int rounds_per_launch = 1) {
+           long long chunk_cols, hipStream_t stream, StepParams& p, TableCtx* tc, double bytes_per_chunk,
+           int rounds_per_launch = 1) {
   if (chunks <= 0) return BSGD_OK;
   if (first_chunk + chunks > 0x7fffffffLL || first_slot + chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   const bool multi = tc != nullptr;
   // near-equal launches of one resident round (times rounds_per_launch) each; the round depends on the dynamic LDS
   auto launch_size = [&](size_t lds) {
     long long round = rounds_per_launch * round_size(fn, block, lds);
-    if (2 * chunks < 5 * round) round = chunks;      // small problems are launch-bound: one launch
+    if (rounds_per_launch == 1 ? one_launch(fn, block, lds, chunks, bytes_per_chunk) : 2 * chunks < 5 * round)
+      round = chunks;
     const long long launches = (chunks + round - 1) / round;
     return (chunks + launches - 1) / launches;
   };
@@ -604,10 +621,11 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   TableCtx table{&plan, reinterpret_cast<Segment*>(ws + L.table_off), reinterpret_cast<unsigned*>(ws + L.starts_off), false};
   TableCtx* tc = multi ? &table : nullptr;
 
-  // Rounds pay when many rows are walked in step.  With few rows the traffic is mostly theta/state, a large
-  // share of it written, and one long launch streams that faster (measured at P = 25 M: N = 1: +12..27 %,
-  // N = 4: +6..9 %, N = 8: +1 %, N = 16: -1..-7 %).
-  const int row_rounds = row_cap <= kFewRows ? (1 << 20) : 1;
+  // bytes a chunk of each pass moves: kept rows plus theta/state streams
+  const int state_streams = 2 * (1 + mode + ema);      // read and written: theta, s0, s1, moving average
+  const double col_bytes = 4.0 * (double)chunk_cols;
+  const double rows_pass_bytes = col_bytes * (row_cap + (clip ? 1 : state_streams));
+  const double rowsq_pass_bytes = col_bytes * row_cap;
   // only chunks that hold columns of some tensor are launched; the per-chunk partial sums are indexed by launch order
   const std::vector<Run> runs = chunk_runs(plan, p.base, chunk_cols, total_chunks);
   long long slots = 0;
@@ -618,7 +636,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   const StepKernel first_pass_sel = clip ? var.reduce_sel[multi ? 1 : 0] : var.rows_sel[mode][multi ? 1 : 0][ema];
   bool fuse = job != nullptr && first_pass_sel != nullptr && job->W <= 64 && !wclip && runs.size() == 1 &&
               g_fuse_select.load(std::memory_order_relaxed) != 0;
-  if (fuse) fuse = row_cap <= kFewRows || 2 * total_chunks < 5 * round_size(first_pass_sel, var.BS, 0);
+  if (fuse) fuse = one_launch(first_pass_sel, var.BS, 0, total_chunks, rows_pass_bytes);
   if (job != nullptr && !fuse) {
     const int rc = enqueue_select_job(N, *job, stream);
     if (rc != BSGD_OK) return rc;
@@ -627,10 +645,10 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
     p.job = *job;
     t_last_fused = 1;
   }
-  auto launch_runs = [&](StepKernel fn, int rounds) {
+  auto launch_runs = [&](StepKernel fn, double bytes_per_chunk, int rounds) {
     long long slot = 0;
     for (const Run& r : runs) {
-      const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, rounds);
+      const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, bytes_per_chunk, rounds);
       if (rc != BSGD_OK) return rc;
       slot += r.count;
     }
@@ -638,22 +656,23 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   };
   if (wclip) {
     // per-worker clipping: every kept row's norm first (one more pass over the kept rows), then its scale
-    int rc = launch_runs(var.rowsq[multi ? 1 : 0], row_rounds);
+    int rc = launch_runs(var.rowsq[multi ? 1 : 0], rowsq_pass_bytes, 1);
     if (rc != BSGD_OK) return rc;
     hipLaunchKernelGGL(k_row_scales, dim3((unsigned)row_cap), dim3(kRowScaleBlock), 0, stream,
                        (const double*)p.row_partials, (int)slots, (int)row_cap, (int)N, (const int*)n_dev,
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  if (!clip) return launch_runs(fuse ? first_pass_sel : first_pass, fuse ? (1 << 20) : row_rounds);
+  // (with the selection inside, one_launch() has said yes above; the huge round count only restates it)
+  if (!clip) return launch_runs(fuse ? first_pass_sel : first_pass, rows_pass_bytes, fuse ? (1 << 20) : 1);
 
-  int rc = launch_runs(fuse ? first_pass_sel : first_pass, fuse ? (1 << 20) : row_rounds);
+  int rc = launch_runs(fuse ? first_pass_sel : first_pass, rows_pass_bytes, fuse ? (1 << 20) : 1);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)slots, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   // the second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails
-  return launch_runs(var.apply[mode][multi ? 1 : 0][ema], kApplyRoundsPerLaunch);
+  return launch_runs(var.apply[mode][multi ? 1 : 0][ema], 0.0, kApplyRoundsPerLaunch);
 }
 
 int bsgd_reduce_update(const float* grads, int64_t ld, const int32_t* sel_idx, const int32_t* status, int32_t N,

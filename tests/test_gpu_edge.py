@@ -67,6 +67,7 @@ class Case:
         self.abs_sum = np.zeros(sum(n for _, n in layout))
         self.max_kept = N
         self.accounted = False
+        self.steps = 0
 
     def draw(self, sigma=0.01, bias=0.0):
         g = np.zeros((self.W, self.ld), np.float32)
@@ -105,6 +106,7 @@ class Case:
     def account(self, g, rows):
         """Adds |g| of the given gradient rows (those a step just summed) to the per-element error budget."""
         rows = [int(k) for k in rows]
+        self.steps += 1
         self.max_kept = max(self.max_kept, len(rows))
         o = 0
         for off, n in self.layout:
@@ -136,7 +138,10 @@ class Case:
                 assert not err.any(), nm
             if nm == "theta":
                 assert self.accounted, "compare() needs the steps' gradients (both() or account())"
-                bound = ELEM_FACTOR * self.max_kept * self.abs_sum
+                # plus what storing theta in fp32 after every step costs whatever the gradients are (half an ulp
+                # each time): with few kept rows and millions of elements some element's gradients are all tiny
+                # and the first term alone falls below the rounding of the store
+                bound = ELEM_FACTOR * self.max_kept * self.abs_sum + self.steps * 2.0 ** -24 * np.abs(ref)
                 worst = float(np.max(np.abs(err) / np.maximum(bound, 1e-300))) if err.size else 0.0
                 assert worst <= 1.0, f"theta: per-element error is {worst:.3f}x the bound"
 
@@ -653,8 +658,13 @@ def test_selection_stays_a_kernel_of_its_own_where_the_step_is_not_one_small_lau
     c = Case(5, 2, [(0, 3001)], "sgd", seed=97, hyper=dict(worker_clip_norm=0.5))
     c.both(*c.draw())
     assert not bs.bsgd_last_step_fused_selection()
-    # several launches (many rows, more than 2.5 rounds of narrow chunks)
-    c = Case(12, 2, [(0, 1_500_000)], "sgd", seed=98)
+    # tensors far apart: the call is two runs of chunks, hence at least two launches
+    c = Case(5, 2, [(0, 3001), (1_200_000, 3001)], "sgd", seed=98)
+    c.both(*c.draw())
+    assert not bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() == 2
+    c.compare()
+    # many rows over many columns: rounds of the wide shape
+    c = Case(40, 2, [(0, 5_400_000)], "rmsprop_mom", seed=99)
     c.both(*c.draw())
     assert not bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() >= 2
     c.compare()
@@ -678,14 +688,15 @@ def _irregular_layout(total, count, seed, crowded=0):
 @pytest.mark.parametrize("crowded", [0, 200])
 @pytest.mark.parametrize("clip", [0.0, 0.004])
 def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip, N):
-    # 1.4 M columns go out as several launches of the narrow shape; each launch sees its own window of the table.
+    # 11 M columns in the widest shape go out as three launches; each launch sees its own window of the table.
     # crowded = 0: every window fits the argument buffer; crowded = 200: the first window does not, so the call
-    # writes the table into the workspace.  Forcing the workspace path must not change a bit.  With N = 3 kept rows
-    # the same columns go out as one launch (few rows: no rounds), whose window holds every segment.
+    # writes the table into the workspace.  Forcing the workspace path must not change a bit.  With N = 3 kept rows,
+    # and in the clipped variants, 1.4 M columns go out as one launch per pass, whose window holds every segment.
     import paper_1604_00981_amd as bs
-    layout = _irregular_layout(1_400_000, 120, seed=31, crowded=crowded)
+    layout = _irregular_layout(11_000_000 if (N > 8 and clip == 0.0) else 1_400_000, 120, seed=31, crowded=crowded)
     results, launches = [], []
     try:
+        bs.bsgd_set_tuning(256, 8, 2, 1)
         for mode in (0, 1):
             bs.bsgd_set_table_mode(mode)
             c = Case(N, 1, layout, "rmsprop_mom", seed=32, hyper=dict(clip_norm=clip))
@@ -696,10 +707,9 @@ def test_tensor_table_as_argument_or_through_workspace_same_bits(crowded, clip, 
             results.append(c.gpu_arrays())
     finally:
         bs.bsgd_set_table_mode(0)
-    if N > 8:
-        assert launches[0] >= 3                         # the windows differ from launch to launch
-    elif clip == 0.0:
-        assert launches[0] == 1
+        bs.bsgd_set_tuning()
+    if clip == 0.0:
+        assert launches[0] == (3 if N > 8 else 1)       # three launches: the windows differ from launch to launch
     for k in results[0]:
         assert np.array_equal(results[0][k], results[1][k]), k
 
