@@ -9,8 +9,6 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
-#include <cstdlib>
-#include <cstring>
 #include <mutex>
 #include <utility>
 #include <vector>

@@ -14,6 +14,10 @@
 //   k_row_sumsq / k_row_scales   per-worker clipping (Appendix A.3 as printed).
 //   k_precombine / k_machine_arrival   one message per machine (Sec. 6).
 //   k_kth_times / k_mean_kth     time to collect k gradients (Sec. 3.1).
+//   k_calibration_copy / k_yardstick   measurement aids: plain copies and
+//                    plain streaming kernels with a chosen mix of streams.
+// A step small enough to be one launch does its selection inside k_step
+// (select_wave is shared by k_select and k_step<..., SELECT>).
 #pragma once
 
 #include <hip/hip_runtime.h>
