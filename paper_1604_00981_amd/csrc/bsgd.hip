@@ -318,14 +318,6 @@ void segment_window(const Plan& plan, long long lo, long long hi, int* j0, int* 
   *j1 = (int)(std::upper_bound(st.begin(), st.begin() + plan.S, (unsigned)(hi - 1)) - st.begin()) - 1;
 }
 
-// Enqueue the work on `chunks` chunks of `chunk_cols` columns, one chunk per
-// workgroup, as a sequence of near-equal launches of at most
-// `rounds_per_launch` rounds of workgroups each.  With several tensors
-// (tc != null) every launch carries the segments its columns fall into as an
-// argument; only when some launch would need more than fit there, the whole
-// table goes through the workspace instead (written once per call).
-// The chunks are first_chunk .. first_chunk+chunks-1 of the call's column
-// space; their slots in the per-chunk partial-sum arrays start at first_slot.
 // A pass goes out as ONE launch when it is small (under 2.5 rounds of chunks, or everything resident at once:
 // launch boundaries then cost more than they bring), or when a round of it moves so little that a boundary costs
 // more than letting workgroups drift (few kept rows, narrow chunks).  Measured with RMSProp-mom: wide chunks at
@@ -340,6 +332,14 @@ bool one_launch(StepKernel fn, int block, size_t lds, long long chunks, double b
   return chunks <= resident || 2 * chunks < 5 * round || bytes_per_chunk * (double)round < kLightRoundBytes;
 }
 
+// Enqueue the work on `chunks` chunks of `chunk_cols` columns, one chunk per
+// workgroup, as a sequence of near-equal launches of at most
+// `rounds_per_launch` rounds of workgroups each.  With several tensors
+// (tc != null) every launch carries the segments its columns fall into as an
+// argument; only when some launch would need more than fit there, the whole
+// table goes through the workspace instead (written once per call).
+// The chunks are first_chunk .. first_chunk+chunks-1 of the call's column
+// space; their slots in the per-chunk partial-sum arrays start at first_slot.
 // bytes_per_chunk: what the pass reads and writes per chunk (decides between one launch and rounds); 0 with
 // rounds_per_launch > 1 for a pass that has its own launch length.
 int launch(StepKernel fn, int block, long long first_chunk, long long first_slot, long long chunks,

@@ -670,6 +670,61 @@ def test_selection_stays_a_kernel_of_its_own_where_the_step_is_not_one_small_lau
     c.compare()
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configurations_against_the_oracle(seed):
+    # every option drawn at random and combined freely: optimizer, clip of the mean, per-worker clip, moving average,
+    # tags, deadline mode, number of workers (up to 256), layout (single or many tensors, gaps, unaligned starts,
+    # misaligned allocations), row stride padding, launch shape (automatic or any compiled one)
+    import paper_1604_00981_amd as bs
+    r = np.random.default_rng(1000 + seed)
+    W = int(r.choice([2, 5, 9, 33, 64, 65, 130, 256]))
+    N = int(r.integers(1, W + 1))
+    b = W - N
+    opt = str(r.choice(["sgd", "momentum", "rmsprop_mom"]))
+    T = int(r.choice([1, 1, 2, 7, 40]))
+    total = int(r.choice([700, 9_000, 70_000]) if W > 64 else r.choice([700, 9_000, 70_000, 400_000]))
+    cuts = np.sort(r.choice(np.arange(1, total), T - 1, replace=False)) if T > 1 else np.array([], int)
+    sizes = [int(x) for x in np.diff(np.concatenate([[0], cuts, [total]]))]
+    layout, o = [], int(r.integers(0, 7))
+    for n in sizes:
+        layout.append((o, n))
+        o += n + (int(r.integers(1, 3000)) if r.random() < 0.3 else 0)
+    span = layout[-1][0] + layout[-1][1]
+    hyper = {}
+    sigma = 0.01
+    if r.random() < 0.4:
+        hyper["clip_norm"] = float(sigma * np.sqrt(sum(sizes) / N) * r.uniform(0.3, 1.5))      # around the norm of the mean
+    if r.random() < 0.35:
+        hyper["worker_clip_norm"] = float(sigma * np.sqrt(sum(sizes)) * r.uniform(0.6, 1.6))   # around a row's norm
+    ema = float(r.choice([0.0, 0.5, 0.9999])) if r.random() < 0.4 else None
+    ld = (span + 3) // 4 * 4 + 4 * int(r.integers(0, 5))
+    shapes = [None] + [bs.bsgd_get_shape(i) for i in range(bs.bsgd_num_shapes())]
+    shape = shapes[int(r.integers(0, len(shapes)))]
+    use_tags, use_deadline = r.random() < 0.3, r.random() < 0.3
+    try:
+        if shape is not None:
+            bs.bsgd_set_tuning(*shape)
+        c = Case(N, b, layout, opt, seed=2000 + seed, ld=ld, theta_shift=int(r.integers(0, 4)), hyper=hyper, ema=ema)
+        done = 0
+        for step in range(3):
+            g, t = c.draw(sigma=sigma)
+            g *= c.r.uniform(0.5, 2.0, (c.W, 1)).astype(np.float32)
+            opts = None
+            if use_tags or use_deadline:
+                opts = {}
+                if use_tags:
+                    opts.update(tags=np.where(c.r.random(W) < 0.15, step - 1, step).astype(np.int32), step_tag=step)
+                if use_deadline:
+                    opts.update(deadline=float(np.sort(t)[int(c.r.integers(0, W))]), n_min=int(c.r.integers(1, N + 1)))
+            status = c.both(g, t, opts)                 # kept set, t_step, status and kept count against the oracle
+            assert status in (0, bs.BSGD_ERR_TOO_FEW)
+            done += status == 0
+        if done:
+            c.compare()
+    finally:
+        bs.bsgd_set_tuning()
+
+
 def _irregular_layout(total, count, seed, crowded=0):
     """`count` tensors of irregular sizes packed back to back over about `total` columns; with `crowded`, that many
     tiny tensors come first (more than one launch can carry as an argument)."""
