@@ -383,9 +383,7 @@ int launch(StepKernel fn, int block, long long first_chunk, long long first_slot
 
   EmbeddedTable et;                                   // filled per launch when the table travels as an argument
   NoTable none{};
-  const long long n_launches = (chunks + per - 1) / per;
-  for (long long li = 0; li < n_launches; ++li) {
-    const long long first = (p.reverse ? n_launches - 1 - li : li) * per;   // reverse: last columns first
+  for (long long first = 0; first < chunks; first += per) {
     const long long n = chunks - first < per ? chunks - first : per;
     ++t_last_launches;
     p.chunk_base = (int)(first_chunk + first);
@@ -647,9 +645,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   }
   auto launch_runs = [&](StepKernel fn, double bytes_per_chunk, int rounds) {
     long long slot = 0;
-    for (size_t i = 0; i < runs.size(); ++i) {
-      if (p.reverse) slot = 0;                         // (a pass walked backwards uses no per-chunk slots)
-      const Run& r = runs[p.reverse ? runs.size() - 1 - i : i];
+    for (const Run& r : runs) {
       const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, bytes_per_chunk, rounds);
       if (rc != BSGD_OK) return rc;
       slot += r.count;
@@ -673,10 +669,7 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)slots, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));
   if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
-  // The second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails.  It walks the
-  // columns from the last to the first: what the first pass stored last is what the second reads first, while
-  // some of it is still in the memory-side cache (measured on 134 M columns: 1 % of the step).
-  p.reverse = 1;
+  // the second pass has no row loop to keep in step: longer launches, fewer ramp-ups and tails
   return launch_runs(var.apply[mode][multi ? 1 : 0][ema], 0.0, kApplyRoundsPerLaunch);
 }
 

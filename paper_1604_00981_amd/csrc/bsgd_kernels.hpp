@@ -293,7 +293,6 @@ struct StepParams {
   int chunk_base;            // chunk id of workgroup 0 of this launch
   int slot_base;             // index of workgroup 0's slot in partials / row_partials (chunks that hold no tensor
                              // are not launched and have no slot)
-  int reverse;               // workgroup i of n takes chunk chunk_base + n-1-i instead of chunk_base + i
   SelectJob job;             // kernels with SELECT: the selection is theirs to do (sel_idx, status, n_dev, div_dev unused)
 };
 
@@ -662,8 +661,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
   const long long span_end4 = (p.col_hi + 3) & ~3LL;   // rows are readable up to here (<= ld)
 
   {
-    // one chunk per workgroup
-    const int chunk_id = (p.reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x) + p.chunk_base;
+    const int chunk_id = (int)blockIdx.x + p.chunk_base;   // one chunk per workgroup
     const long long c0 = p.base + (long long)chunk_id * CH;   // first column of the chunk, multiple of 4
 
     // the segment holding the chunk's first column (clamped into the covered range)
