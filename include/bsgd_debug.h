@@ -64,13 +64,13 @@ int bsgd_last_launch_count(void);
 int bsgd_debug_chunk_runs(const bsgd_tensor* tensors, int32_t T, int64_t chunk_cols, int64_t* first, int64_t* count,
                           int32_t capacity, int32_t* n_runs);
 
-/* A step small enough to go out as one launch (at most 64 workers, the narrow
- * launch shape, no per-worker clipping) does its selection inside that launch
- * instead of in a kernel of its own; results and everything the bsgd_last_*
- * getters report are the same either way.  bsgd_set_fused_selection(0) makes
- * every step use the separate selection kernel (process-wide; 1 = default);
- * bsgd_last_step_fused_selection tells whether the calling thread's last
- * bsgd_step / bsgd_step_ex / bsgd_step_noalloc did it inside (1) or not (0). */
+/* A step with at most 64 workers and no per-worker clipping does its selection
+ * inside its first launch instead of in a kernel of its own; results and
+ * everything the bsgd_last_* getters report are the same either way.
+ * bsgd_set_fused_selection(0) makes every step use the separate selection
+ * kernel (process-wide; 1 = default); bsgd_last_step_fused_selection tells
+ * whether the calling thread's last bsgd_step / bsgd_step_ex /
+ * bsgd_step_noalloc did it inside (1) or not (0). */
 int bsgd_set_fused_selection(int32_t on);
 int bsgd_last_step_fused_selection(void);
 

@@ -48,7 +48,7 @@ struct Variant {
   StepKernel reduce[2];      // [multi]              clipped step, pass 1: mean + sum of squares
   StepKernel rowsq[2];       // [multi]              per-worker clipping: per-row sums of squares
   StepKernel apply[3][2][2]; // [mode][multi][ema]   clipped step, pass 2: gradient from the stored mean
-  // the same first passes doing the selection themselves (one-launch steps; narrow shape only, else null)
+  // the same first passes doing the selection themselves (the first launch of a step; null for the plain-load shape)
   StepKernel rows_sel[3][2][2];
   StepKernel reduce_sel[2];
 };
@@ -75,7 +75,7 @@ Variant make_variant() {
   v.reduce[1] = reinterpret_cast<StepKernel>(&k_step<kClipReduce, R, true, true, false>);
   v.rowsq[0] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, false>);
   v.rowsq[1] = reinterpret_cast<StepKernel>(&k_row_sumsq<R, true>);
-  if constexpr (V == 1 && NT != 0) {
+  if constexpr (NT != 0) {
 #define BSGD_FILL_SEL(dst, MODE)                                                               \
   dst[0][0] = reinterpret_cast<StepKernel>(&k_step<MODE, R, false, true, false, true>);        \
   dst[0][1] = reinterpret_cast<StepKernel>(&k_step<MODE, R, false, true, true, true>);         \
@@ -342,9 +342,10 @@ bool one_launch(StepKernel fn, int block, size_t lds, long long chunks, double b
 // space; their slots in the per-chunk partial-sum arrays start at first_slot.
 // bytes_per_chunk: what the pass reads and writes per chunk (decides between one launch and rounds); 0 with
 // rounds_per_launch > 1 for a pass that has its own launch length.
+// first_fn: when set, the kernel of the first launch (the variant of fn that does the step's selection itself).
 int launch(StepKernel fn, int block, long long first_chunk, long long first_slot, long long chunks,
            long long chunk_cols, hipStream_t stream, StepParams& p, TableCtx* tc, double bytes_per_chunk,
-           int rounds_per_launch = 1) {
+           int rounds_per_launch = 1, StepKernel first_fn = nullptr) {
   if (chunks <= 0) return BSGD_OK;
   if (first_chunk + chunks > 0x7fffffffLL || first_slot + chunks > 0x7fffffffLL || fn == nullptr) return BSGD_ERR_ARG;
   const bool multi = tc != nullptr;
@@ -414,7 +415,8 @@ int launch(StepKernel fn, int block, long long first_chunk, long long first_slot
       second = &et;
     }
     void* args[] = {&p, second};
-    hipError_t e = hipLaunchKernel(fn, dim3((unsigned)n), dim3(block), args, lds, stream);
+    hipError_t e = hipLaunchKernel(first == 0 && first_fn != nullptr ? first_fn : fn, dim3((unsigned)n), dim3(block),
+                                   args, lds, stream);
     if (e != hipSuccess) return BSGD_ERR_HIP;
   }
   return BSGD_OK;
@@ -628,13 +630,13 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
   const std::vector<Run> runs = chunk_runs(plan, p.base, chunk_cols, total_chunks);
   long long slots = 0;
   for (const Run& r : runs) slots += r.count;
-  // The selection inside the step's launch: one run, one launch, at most 64 workers, no per-worker clip (its
-  // norm pass needs the kept rows first).
+  // The selection inside the step's first launch: at most 64 workers, no per-worker clip (its norm pass needs
+  // the kept rows first).  Every workgroup of that launch ranks the arrival times for itself; its first one
+  // publishes the kept rows and the status, which the step's later launches read like k_select's.
   const StepKernel first_pass = clip ? var.reduce[multi ? 1 : 0] : var.rows[mode][multi ? 1 : 0][ema];
   const StepKernel first_pass_sel = clip ? var.reduce_sel[multi ? 1 : 0] : var.rows_sel[mode][multi ? 1 : 0][ema];
-  bool fuse = job != nullptr && first_pass_sel != nullptr && job->W <= 64 && !wclip && runs.size() == 1 &&
-              g_fuse_select.load(std::memory_order_relaxed) != 0;
-  if (fuse) fuse = one_launch(first_pass_sel, var.BS, 0, total_chunks, rows_pass_bytes);
+  const bool fuse = job != nullptr && first_pass_sel != nullptr && job->W <= 64 && !wclip &&
+                    g_fuse_select.load(std::memory_order_relaxed) != 0;
   if (job != nullptr && !fuse) {
     const int rc = enqueue_select_job(N, *job, stream);
     if (rc != BSGD_OK) return rc;
@@ -643,10 +645,11 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
     p.job = *job;
     t_last_fused = 1;
   }
-  auto launch_runs = [&](StepKernel fn, double bytes_per_chunk, int rounds) {
+  auto launch_runs = [&](StepKernel fn, double bytes_per_chunk, int rounds, StepKernel first_fn = nullptr) {
     long long slot = 0;
     for (const Run& r : runs) {
-      const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, bytes_per_chunk, rounds);
+      const int rc = launch(fn, var.BS, r.first, slot, r.count, chunk_cols, stream, p, tc, bytes_per_chunk, rounds,
+                            slot == 0 ? first_fn : nullptr);
       if (rc != BSGD_OK) return rc;
       slot += r.count;
     }
@@ -661,10 +664,9 @@ static int enqueue_update(const float* grads, int64_t ld, const int32_t* sel_idx
                        hyper->worker_clip_norm, (const int*)status, reinterpret_cast<float*>(ws + L.rowscale_off));
     if (hipGetLastError() != hipSuccess) return BSGD_ERR_HIP;
   }
-  // (with the selection inside, one_launch() has said yes above; the huge round count only restates it)
-  if (!clip) return launch_runs(fuse ? first_pass_sel : first_pass, rows_pass_bytes, fuse ? (1 << 20) : 1);
+  if (!clip) return launch_runs(first_pass, rows_pass_bytes, 1, fuse ? first_pass_sel : nullptr);
 
-  int rc = launch_runs(fuse ? first_pass_sel : first_pass, rows_pass_bytes, fuse ? (1 << 20) : 1);
+  int rc = launch_runs(first_pass, rows_pass_bytes, 1, fuse ? first_pass_sel : nullptr);
   if (rc != BSGD_OK) return rc;
   hipLaunchKernelGGL(k_finalize_norm, dim3(1), dim3(kFinalizeBlock), 0, stream, (const double*)p.partials,
                      (int)slots, hyper->clip_norm, (const int*)status, reinterpret_cast<WsHeader*>(ws));

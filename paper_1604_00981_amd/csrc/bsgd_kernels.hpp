@@ -248,12 +248,13 @@ __global__ __launch_bounds__(64) void k_select(const float* __restrict__ arrival
   select_wave<R, DPP>(arrival_t, N, W, o, sel_idx, n_kept, t_step, status);
 }
 
-// The selection as part of a step that goes out as ONE launch (small
-// problems, where a launch of its own for k_select is a third of the step):
-// every wavefront of the step's kernel ranks the W <= 64 arrival times itself
-// (DPP rotates only: no LDS, no barrier, no other wavefront to wait for) and
-// takes the kept rows from the resulting 64-bit mask; the first wavefront of
-// the launch also publishes what k_select would have written.
+// The selection as part of a step's first launch (no launch of its own for
+// k_select, which is a third of a small step and 4 us of a large one):
+// every wavefront of that launch ranks the W <= 64 arrival times itself (DPP
+// rotates or scalar broadcasts only: no LDS, no barrier, no other wavefront to
+// wait for) and takes the kept rows from the resulting 64-bit mask; the first
+// wavefront of the launch also publishes what k_select would have written,
+// and the step's later launches (if any) read that.
 struct SelectJob {
   const float* arrival_t;
   int W;
@@ -621,7 +622,7 @@ __device__ __forceinline__ int find_segment(const unsigned* starts, int S, unsig
 // (nearly all of them) takes the uniform path with wave-uniform pointers and
 // float4 accesses (4-byte aligned only, since a tensor may start anywhere in
 // the row); a chunk holding a tensor boundary looks segments up per lane.
-// SELECT (with SRC_ROWS): the launch is the whole step and does the selection itself, see SelectJob.
+// SELECT (with SRC_ROWS): the launch is a step's first and does the selection itself, see SelectJob.
 template <int MODE, class S, bool MULTI, bool SRC_ROWS, bool EMA, bool SELECT = false>
 __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
   static_assert(!SELECT || SRC_ROWS, "only a pass over the gradient rows can do the selection");
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(S::BS) void k_step(StepParams p, TableArg<MULTI>) {
   float inv_n;
   unsigned long long row_mask = 0;
   if constexpr (SELECT) {
-    const bool publish = blockIdx.x == 0 && threadIdx.x < 64;   // one wavefront of the (single) launch writes the outputs
+    const bool publish = blockIdx.x == 0 && threadIdx.x < 64;   // one wavefront of the launch writes the outputs
     SelectOpts o = p.job.opts;
     if (!publish) o.n_grad = nullptr;
     const Selected sel = select_wave<1, true>(p.job.arrival_t, p.N, p.job.W, o, publish ? p.job.sel_idx : nullptr,

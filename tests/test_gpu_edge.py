@@ -608,8 +608,8 @@ _FUSED_KINDS = {
 
 @pytest.mark.parametrize("kind", sorted(_FUSED_KINDS))
 def test_selection_inside_the_step_launch_equals_the_separate_kernel(kind):
-    # A small step goes out as one launch that ranks the arrival times itself (every wavefront, from a 64-bit mask of
-    # the kept rows); with that switched off the same step runs k_select first.  Same bits, same recorded outputs;
+    # A step's first launch ranks the arrival times itself (every wavefront, from a 64-bit mask of the kept rows);
+    # with that switched off the same step runs k_select first.  Same bits, same recorded outputs;
     # both against the oracle.  Then too few arrivals: nothing may be touched either way.
     import paper_1604_00981_amd as bs
     N, b, layout, opt, hyper, ema, sel_mode = _FUSED_KINDS[kind]
@@ -648,26 +648,48 @@ def test_selection_inside_the_step_launch_equals_the_separate_kernel(kind):
         assert np.array_equal(out[True][0][k], out[False][0][k]), k
 
 
-def test_selection_stays_a_kernel_of_its_own_where_the_step_is_not_one_small_launch():
+def test_where_the_selection_runs():
     import paper_1604_00981_amd as bs
-    # more than 64 workers
+    # more than 64 workers: a kernel of its own
     c = Case(70, 5, [(0, 3001)], "sgd", seed=96)
     c.both(*c.draw())
     assert not bs.bsgd_last_step_fused_selection()
-    # per-worker clipping needs the kept rows before its norm pass
+    # per-worker clipping needs the kept rows before its norm pass: a kernel of its own
     c = Case(5, 2, [(0, 3001)], "sgd", seed=97, hyper=dict(worker_clip_norm=0.5))
     c.both(*c.draw())
     assert not bs.bsgd_last_step_fused_selection()
-    # tensors far apart: the call is two runs of chunks, hence at least two launches
+    # tensors far apart: two runs of chunks, two launches; the first does the selection, the second reads what it published
     c = Case(5, 2, [(0, 3001), (1_200_000, 3001)], "sgd", seed=98)
-    c.both(*c.draw())
-    assert not bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() == 2
+    for _ in range(2):
+        c.both(*c.draw())
+    assert bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() == 2
     c.compare()
-    # many rows over many columns: rounds of the wide shape
+    # many rows over many columns: several rounds; again only the first launch ranks the arrival times
     c = Case(40, 2, [(0, 5_400_000)], "rmsprop_mom", seed=99)
-    c.both(*c.draw())
-    assert not bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() >= 2
+    for _ in range(2):
+        c.both(*c.draw())
+    assert bs.bsgd_last_step_fused_selection() and bs.bsgd_last_launch_count() >= 2
     c.compare()
+    # ... and when too few arrive, no launch of the step touches anything
+    before = c.gpu_arrays()
+    g, t = c.draw()
+    t[:3] = np.inf
+    assert c.both(g, t) == bs.BSGD_ERR_TOO_FEW
+    after = c.gpu_arrays()
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k
+    # the same large step with the selection as a kernel of its own: the same bits
+    try:
+        bs.bsgd_set_fused_selection(False)
+        d = Case(40, 2, [(0, 5_400_000)], "rmsprop_mom", seed=99)
+        for _ in range(2):
+            d.both(*d.draw())
+        assert not bs.bsgd_last_step_fused_selection()
+    finally:
+        bs.bsgd_set_fused_selection(True)
+    gd = d.gpu_arrays()
+    for k in before:
+        assert np.array_equal(before[k], gd[k]), k
 
 
 @pytest.mark.parametrize("seed", range(48))
